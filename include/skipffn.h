@@ -1,0 +1,165 @@
+/*
+ * skipffn.h - C ABI of the MI355X (gfx950) Skip-FFN block.
+ *
+ * The block is the feed-forward half of one decoder layer under Skip-Vision
+ * (Section 4.2 of the paper, "Training speed-up: skip FFN"):
+ *
+ *     retained token :  h_out = h_attn + FFN(h_attn)
+ *     skipped  token :  h_out = h_attn
+ *
+ * with FFN the pre-norm SwiGLU MLP of the paper's LLaMA-3-8B backbone
+ * (Section 5.4; three C x M matrices, cf. the 3*N2*C*M term of Section 5.2 and
+ * Table 1):  FFN(x) = W_down( silu(W_gate n(x)) * (W_up n(x)) ),
+ * n(x) = x * rsqrt(mean(x^2) + eps) * gain.
+ *
+ * Conventions common to every call
+ * --------------------------------
+ *  - All tensor pointers are DEVICE pointers (HBM of the current HIP device)
+ *    unless a parameter says "host".  Tensors are dense row-major.
+ *  - bf16 tensors are passed as `const void*` / `void*` to 16-bit elements
+ *    (the upper half of an IEEE binary32).  Accumulation is fp32.
+ *  - T = tokens in the flattened (packed, unpadded) batch, R = retained rows,
+ *    C = hidden size, I = intermediate size (the paper's M).
+ *    C % 8 == 0, I % 8 == 0; every tensor pointer is 16-byte aligned.
+ *  - Weights use the [out_features, in_features] layout: w_gate, w_up [I, C],
+ *    w_down [C, I]  (y = x W^T).  No pre-packing.
+ *  - skip_mask: one byte per token, non-zero = the token skips the FFN.
+ *  - idx: ascending token indices of the retained rows (what skipffn_compact
+ *    writes).  `R` is given by the host (R >= 0); or R = -1 and `num_retained`
+ *    points at the device-side count written by skipffn_compact, in which case
+ *    no host synchronisation happens and buffers must be sized for R = T.
+ *  - Ownership: the caller owns every buffer.  The library allocates no
+ *    device memory, keeps no pointer after a call returns, never synchronises
+ *    the device and enqueues work only on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream).  Results are complete when the stream
+ *    reaches the end of the enqueued work.
+ *  - Every function returns a skipffn_status; 0 is success.  Argument errors
+ *    are detected on the host before anything is enqueued.  Nothing aborts,
+ *    throws or prints.
+ */
+#ifndef SKIPFFN_H
+#define SKIPFFN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum skipffn_status {
+    SKIPFFN_OK = 0,
+    SKIPFFN_EINVAL = 1,       /* null / misaligned pointer, negative size, R > T */
+    SKIPFFN_ESHAPE = 2,       /* C or I not a multiple of 8, or a tensor >= 2 GiB */
+    SKIPFFN_EWORKSPACE = 3,   /* workspace (or saved buffer) too small */
+    SKIPFFN_EHIP = 4,         /* a HIP call failed; see skipffn_last_hip_error */
+    SKIPFFN_EUNSUPPORTED = 5  /* unknown flag bit */
+} skipffn_status;
+
+/* flags (bitwise or) */
+#define SKIPFFN_FLAG_DW_FP32        0x1u  /* backward: dw_* are float32, not bf16 */
+#define SKIPFFN_FLAG_DW_ACCUMULATE  0x2u  /* backward: dw_* += instead of = */
+#define SKIPFFN_FLAG_NO_RESIDUAL    0x4u  /* forward: retained rows get bf16(FFN(x)), not bf16(x + FFN(x)) - a debugging view */
+#define SKIPFFN_FLAG_ALL            0x7u
+
+/* ---- step 1: mask -> ascending retained indices -------------------------
+ * Section 4.1 decides which visual tokens are retained; the block consumes
+ * that partition.  Writes idx[0..R) = positions t with skip_mask[t] == 0 in
+ * increasing t (entries beyond R are left untouched), *num_retained = R and,
+ * if pos != NULL, pos[t] = compacted row of token t or -1 if skipped.
+ *   skip_mask  u8  [T]  device, 16-byte aligned
+ *   idx        i32 [T]  device OUT (capacity T)
+ *   num_retained i32 [1] device OUT
+ *   pos        i32 [T]  device OUT or NULL
+ *   workspace  device scratch of at least skipffn_compact_workspace_bytes(T)
+ * T == 0 is valid (writes *num_retained = 0).  Deterministic. */
+size_t skipffn_compact_workspace_bytes(int64_t T);
+int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx,
+                    int32_t* num_retained, int32_t* pos,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- steps 2-4: forward of the block (Section 4.2, both equations) --------
+ *   hidden  bf16 [T, C]  input (h_attn)
+ *   out     bf16 [T, C]  output; may be the same pointer as hidden (in place:
+ *                        skipped rows are then not touched at all).  When
+ *                        out != hidden, skipped rows are copied bit for bit.
+ *                        Partial overlap is not allowed.
+ *   idx, R, num_retained : see conventions
+ *   rms_gain bf16 [C] or NULL (= all ones)
+ *   w_gate, w_up bf16 [I, C]; w_down bf16 [C, I]
+ *   saved   NULL, or a buffer of skipffn_saved_bytes(R_max, C, I) bytes that
+ *           receives what backward needs (gathered input rows, normalised
+ *           rows, 1/rms, gate, up and hidden activations); required for
+ *           training because an in-place forward overwrites its input.
+ *   workspace: at least skipffn_forward_workspace_bytes(R_max, C, I, saved != NULL)
+ * where R_max = R if R >= 0 else T.
+ * R == 0 or T == 0: no arithmetic (out-of-place: plain copy). */
+size_t skipffn_saved_bytes(int64_t R_max, int64_t C, int64_t I);
+size_t skipffn_forward_workspace_bytes(int64_t R_max, int64_t C, int64_t I, int has_saved);
+int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps,
+                    const void* hidden, void* out,
+                    const int32_t* idx, int64_t R, const int32_t* num_retained,
+                    const void* rms_gain,
+                    const void* w_gate, const void* w_up, const void* w_down,
+                    void* saved, void* workspace, size_t workspace_bytes,
+                    uint32_t flags, void* stream);
+
+/* ---- step 5: backward over retained rows only -----------------------------
+ * The paper applies the skip during supervised fine-tuning (Section 4.2), so
+ * gradients flow through the FFN for retained tokens only; a skipped token has
+ * an identity Jacobian through this block.
+ *   grad_out    bf16 [T, C]  upstream gradient
+ *   grad_hidden bf16 [T, C]  OUT; may alias grad_out (skipped rows untouched);
+ *                            otherwise skipped rows are bit copies of grad_out
+ *   saved       what the matching forward wrote (same R, C, I)
+ *   dw_gate, dw_up [I, C]; dw_down [C, I]: bf16, overwritten, unless
+ *       SKIPFFN_FLAG_DW_FP32 (float32) / SKIPFFN_FLAG_DW_ACCUMULATE (+=).
+ *       With R == 0 they are zero-filled (or left as they are when
+ *       accumulating).
+ *   workspace: at least skipffn_backward_workspace_bytes(R_max, C, I)
+ * No gradient for rms_gain is produced. */
+size_t skipffn_backward_workspace_bytes(int64_t R_max, int64_t C, int64_t I);
+int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps,
+                     const void* grad_out, void* grad_hidden,
+                     const int32_t* idx, int64_t R, const int32_t* num_retained,
+                     const void* rms_gain,
+                     const void* w_gate, const void* w_up, const void* w_down,
+                     const void* saved,
+                     void* dw_gate, void* dw_up, void* dw_down,
+                     void* workspace, size_t workspace_bytes,
+                     uint32_t flags, void* stream);
+
+/* ---- skip KV-cache (Section 4.3, the set-difference equation) -------------
+ * After prefill the key / value rows of FFN-skipped tokens are dropped:
+ * dst[r, :] = src[idx[r], :] for r < R.  row_bytes % 16 == 0.
+ *   src  [T, row_bytes] device;  dst [R, row_bytes] device OUT (no overlap) */
+int skipffn_gather_rows(const void* src, void* dst, int64_t T, int64_t row_bytes,
+                        const int32_t* idx, int64_t R, const int32_t* num_retained,
+                        void* stream);
+
+/* ---- layout of `saved`, for tests that compare stage by stage -------------
+ * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
+ * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];
+ * [2] 1/rms f32 [R]; [3] gate bf16 [R, I]; [4] up bf16 [R, I];
+ * [5] silu(gate)*up bf16 [R, I].  `offsets` is a HOST array of 6. */
+int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets);
+
+/* ---- diagnostics ---------------------------------------------------------- */
+const char* skipffn_status_string(int status);
+int skipffn_last_hip_error(void);     /* hipError_t of the last SKIPFFN_EHIP on this thread */
+int skipffn_version(void);            /* major * 10000 + minor * 100 + patch */
+
+/* Duration in milliseconds, measured with HIP events on `stream`, of the most
+ * recent launch of each hot-path kernel class since the last
+ * skipffn_profile_begin.  Profiling mode records events around every kernel
+ * launch (it never synchronises inside a forward/backward call);
+ * skipffn_profile_end synchronises those events and fills host arrays.
+ *   names: host array of `cap` const char* (kernel class names, static storage)
+ *   ms, launches: host arrays of `cap`;  returns the number of classes. */
+int skipffn_profile_begin(void);
+int skipffn_profile_end(const char** names, double* ms, int64_t* launches, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKIPFFN_H */

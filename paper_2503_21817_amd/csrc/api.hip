@@ -1,0 +1,481 @@
+// C ABI of the Skip-FFN block: argument validation, workspace carving and the
+// launch sequences of forward and backward.  Declarations and the contract of
+// every entry point are in include/skipffn.h.
+#include <mutex>
+#include <vector>
+
+#include "../../include/skipffn.h"
+#include "kernels.hpp"
+
+using namespace skipffn;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+int hip_fail(hipError_t e) {
+    g_last_hip = (int)e;
+    return SKIPFFN_EHIP;
+}
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool bad_ptr(const void* p) { return p == nullptr || !aligned16(p); }
+constexpr int64_t kMaxTensorBytes = (int64_t)1 << 31;
+
+// ---- event profiler -----------------------------------------------------------------
+struct ProfRec { int kc; hipEvent_t a, b; };
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;
+
+std::once_flag g_gemm_once;
+hipError_t g_gemm_init_err = hipSuccess;
+hipError_t ensure_gemm_init() {
+    std::call_once(g_gemm_once, [] { g_gemm_init_err = gemm_init(); });
+    return g_gemm_init_err;
+}
+
+constexpr int kMaxSplits = 8;
+
+// Split-K factor for a GEMM with `tiles` output tiles and `ktiles` K slabs on 256
+// CUs (one workgroup per CU).  Cost in units of one K slab of one tile: every
+// round of 256 workgroups costs its slab count plus a fixed prologue/epilogue,
+// partial tiles cost a write now and a read in the reducing kernel.
+int choose_splits(int tiles, int ktiles) {
+    int best = 1;
+    double best_cost = 1e30;
+    for (int s = 1; s <= kMaxSplits; ++s) {
+        int per = (ktiles + s - 1) / s;
+        if (s > 1 && per < 8) break;
+        int rounds = (tiles * s + 255) / 256;
+        double cost = rounds * (per + 8.0 + (s > 1 ? 8.0 : 0.0)) + (s > 1 ? 0.04 * s * tiles : 0.0);
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+    }
+    return best;
+}
+
+struct SavedLayout { size_t off[6]; size_t total; };
+SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
+    SavedLayout L;
+    size_t o = 0;
+    L.off[0] = o; o += align_up((size_t)R * C * 2);
+    L.off[1] = o; o += align_up((size_t)R * C * 2);
+    L.off[2] = o; o += align_up((size_t)R * 4);
+    L.off[3] = o; o += align_up((size_t)R * I * 2);
+    L.off[4] = o; o += align_up((size_t)R * I * 2);
+    L.off[5] = o; o += align_up((size_t)R * I * 2);
+    L.total = o;
+    return L;
+}
+
+struct FwdWs { size_t xn, rstd, h, partial, total; };
+FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
+    FwdWs w; size_t o = 0;
+    w.xn = o;   if (!has_saved) o += align_up((size_t)R * C * 2);
+    w.rstd = o; if (!has_saved) o += align_up((size_t)R * 4);
+    w.h = o;    if (!has_saved) o += align_up((size_t)R * I * 2);
+    w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
+    w.total = o;
+    return w;
+}
+
+struct BwdWs { size_t dy, dg, du, partial, total; };
+BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
+    BwdWs w; size_t o = 0;
+    w.dy = o; o += align_up((size_t)R * C * 2);
+    w.dg = o; o += align_up((size_t)R * I * 2);
+    w.du = o; o += align_up((size_t)R * I * 2);
+    w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
+    w.total = o;
+    return w;
+}
+
+int check_common(int64_t T, int64_t C, int64_t I, int64_t R, const int32_t* num_retained,
+                 uint32_t flags) {
+    if (flags & ~SKIPFFN_FLAG_ALL) return SKIPFFN_EUNSUPPORTED;
+    if (T < 0 || C <= 0 || I <= 0 || R < -1 || R > T) return SKIPFFN_EINVAL;
+    if (R == -1 && num_retained == nullptr) return SKIPFFN_EINVAL;
+    if ((C & 7) || (I & 7)) return SKIPFFN_ESHAPE;
+    int64_t Rb = R < 0 ? T : R;
+    if (T * C * 2 >= kMaxTensorBytes || I * C * 2 >= kMaxTensorBytes ||
+        Rb * I * 2 >= kMaxTensorBytes || T > 0x7fffffff)
+        return SKIPFFN_ESHAPE;
+    return SKIPFFN_OK;
+}
+
+bool partial_overlap(const void* a, const void* b, size_t bytes) {
+    if (a == b) return false;
+    uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + bytes && y < x + bytes;
+}
+
+}  // namespace
+
+namespace skipffn {
+
+const char* kernel_class_name(int kc) {
+    static const char* names[KC_COUNT] = {
+        "compact", "gather_rmsnorm", "gemm_gate_up_swiglu", "gemm_down", "resid_scatter",
+        "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd", "gemm_dw_down",
+        "gemm_dw_gate_up", "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero"};
+    return (kc >= 0 && kc < KC_COUNT) ? names[kc] : "?";
+}
+
+void profile_mark_begin(int kc, hipStream_t s) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    ProfRec r; r.kc = kc;
+    if (!g_prof_pool.empty()) {
+        r.a = g_prof_pool.back().first; r.b = g_prof_pool.back().second;
+        g_prof_pool.pop_back();
+    } else {
+        if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) return;
+    }
+    (void)hipEventRecord(r.a, s);
+    g_prof_recs.push_back(r);
+}
+
+void profile_mark_end(int kc, hipStream_t s) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (size_t i = g_prof_recs.size(); i-- > 0;) {
+        if (g_prof_recs[i].kc == kc) { (void)hipEventRecord(g_prof_recs[i].b, s); break; }
+    }
+}
+
+}  // namespace skipffn
+
+extern "C" {
+
+const char* skipffn_status_string(int status) {
+    switch (status) {
+        case SKIPFFN_OK: return "ok";
+        case SKIPFFN_EINVAL: return "invalid argument (null or misaligned pointer, negative size, R > T)";
+        case SKIPFFN_ESHAPE: return "unsupported shape (C, I must be multiples of 8; tensors below 2 GiB)";
+        case SKIPFFN_EWORKSPACE: return "workspace too small";
+        case SKIPFFN_EHIP: return "HIP runtime error";
+        case SKIPFFN_EUNSUPPORTED: return "unsupported flag";
+        default: return "unknown status";
+    }
+}
+
+int skipffn_last_hip_error(void) { return g_last_hip; }
+int skipffn_version(void) { return 100; }
+
+int skipffn_profile_begin(void) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (auto& r : g_prof_recs) g_prof_pool.emplace_back(r.a, r.b);
+    g_prof_recs.clear();
+    g_prof_on = true;
+    return SKIPFFN_OK;
+}
+
+int skipffn_profile_end(const char** names, double* ms, int64_t* launches, int cap) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_on = false;
+    double tot[KC_COUNT] = {0};
+    int64_t cnt[KC_COUNT] = {0};
+    for (auto& r : g_prof_recs) {
+        if (hipEventSynchronize(r.b) != hipSuccess) continue;
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, r.a, r.b) == hipSuccess) { tot[r.kc] += t; cnt[r.kc] += 1; }
+    }
+    for (auto& r : g_prof_recs) g_prof_pool.emplace_back(r.a, r.b);
+    g_prof_recs.clear();
+    int n = KC_COUNT < cap ? KC_COUNT : cap;
+    for (int i = 0; i < n; ++i) {
+        if (names) names[i] = kernel_class_name(i);
+        if (ms) ms[i] = tot[i];
+        if (launches) launches[i] = cnt[i];
+    }
+    return KC_COUNT;
+}
+
+// ---- compaction ------------------------------------------------------------------------
+size_t skipffn_compact_workspace_bytes(int64_t T) { return compact_workspace_bytes(T); }
+
+int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx, int32_t* num_retained,
+                    int32_t* pos, void* workspace, size_t workspace_bytes, void* stream) {
+    if (T < 0 || T > 0x7fffffff || num_retained == nullptr) return SKIPFFN_EINVAL;
+    if (T > 0 && (bad_ptr(skip_mask) || idx == nullptr)) return SKIPFFN_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(idx) & 3u) || (reinterpret_cast<uintptr_t>(pos) & 3u) ||
+        (reinterpret_cast<uintptr_t>(num_retained) & 3u))
+        return SKIPFFN_EINVAL;
+    size_t need = compact_workspace_bytes(T);
+    if (workspace_bytes < need || (need > 0 && workspace == nullptr)) return SKIPFFN_EWORKSPACE;
+    hipError_t e = launch_compact(skip_mask, T, idx, num_retained, pos, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+// ---- sizes --------------------------------------------------------------------------------
+size_t skipffn_saved_bytes(int64_t R_max, int64_t C, int64_t I) {
+    if (R_max < 0 || C <= 0 || I <= 0) return 0;
+    return saved_layout(R_max, C, I).total + 256;
+}
+int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets) {
+    if (R_max < 0 || C <= 0 || I <= 0 || offsets == nullptr) return SKIPFFN_EINVAL;
+    SavedLayout L = saved_layout(R_max, C, I);
+    for (int i = 0; i < 6; ++i) offsets[i] = L.off[i];
+    return SKIPFFN_OK;
+}
+size_t skipffn_forward_workspace_bytes(int64_t R_max, int64_t C, int64_t I, int has_saved) {
+    if (R_max < 0 || C <= 0 || I <= 0) return 0;
+    return fwd_ws(R_max, C, I, has_saved != 0).total + 256;
+}
+size_t skipffn_backward_workspace_bytes(int64_t R_max, int64_t C, int64_t I) {
+    if (R_max < 0 || C <= 0 || I <= 0) return 0;
+    return bwd_ws(R_max, C, I).total + 256;
+}
+
+// ---- forward ---------------------------------------------------------------------------------
+int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidden, void* out,
+                    const int32_t* idx, int64_t R, const int32_t* num_retained,
+                    const void* rms_gain, const void* w_gate, const void* w_up, const void* w_down,
+                    void* saved, void* workspace, size_t workspace_bytes, uint32_t flags,
+                    void* stream) {
+    int st = check_common(T, C, I, R, num_retained, flags);
+    if (st != SKIPFFN_OK) return st;
+    if (!(eps >= 0.0f)) return SKIPFFN_EINVAL;
+    const int64_t Rb = R < 0 ? T : R;
+    if (T > 0 && (bad_ptr(hidden) || bad_ptr(out))) return SKIPFFN_EINVAL;
+    if (T > 0 && partial_overlap(hidden, out, (size_t)T * C * 2)) return SKIPFFN_EINVAL;
+    if (rms_gain != nullptr && !aligned16(rms_gain)) return SKIPFFN_EINVAL;
+    if (saved != nullptr && !aligned16(saved)) return SKIPFFN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t* r_dev = R < 0 ? num_retained : nullptr;
+
+    if (Rb > 0) {
+        if (idx == nullptr || (reinterpret_cast<uintptr_t>(idx) & 3u)) return SKIPFFN_EINVAL;
+        if (bad_ptr(w_gate) || bad_ptr(w_up) || bad_ptr(w_down)) return SKIPFFN_EINVAL;
+        FwdWs W = fwd_ws(Rb, C, I, saved != nullptr);
+        if (workspace == nullptr || !aligned16(workspace)) return SKIPFFN_EWORKSPACE;
+        if (workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
+    }
+    if (T == 0) return SKIPFFN_OK;
+
+    hipError_t e;
+    if (out != hidden) {
+        e = launch_passthrough(hidden, out, T, C * 2, idx, (int)Rb, r_dev, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    if (Rb == 0) return SKIPFFN_OK;
+    if ((e = ensure_gemm_init()) != hipSuccess) return hip_fail(e);
+
+    FwdWs W = fwd_ws(Rb, C, I, saved != nullptr);
+    char* ws = static_cast<char*>(workspace);
+    bf16_t *xrows = nullptr, *xn, *G = nullptr, *U = nullptr, *H;
+    float* rstd;
+    if (saved != nullptr) {
+        SavedLayout L = saved_layout(Rb, C, I);
+        char* sv = static_cast<char*>(saved);
+        xrows = reinterpret_cast<bf16_t*>(sv + L.off[0]);
+        xn = reinterpret_cast<bf16_t*>(sv + L.off[1]);
+        rstd = reinterpret_cast<float*>(sv + L.off[2]);
+        G = reinterpret_cast<bf16_t*>(sv + L.off[3]);
+        U = reinterpret_cast<bf16_t*>(sv + L.off[4]);
+        H = reinterpret_cast<bf16_t*>(sv + L.off[5]);
+    } else {
+        xn = reinterpret_cast<bf16_t*>(ws + W.xn);
+        rstd = reinterpret_cast<float*>(ws + W.rstd);
+        H = reinterpret_cast<bf16_t*>(ws + W.h);
+    }
+    float* partial = reinterpret_cast<float*>(ws + W.partial);
+
+    // (2) gather + RMSNorm
+    e = launch_gather_rmsnorm(static_cast<const bf16_t*>(hidden), idx, (int)Rb, r_dev, (int)C, eps,
+                              static_cast<const bf16_t*>(rms_gain), xrows, xn, rstd, s);
+    if (e != hipSuccess) return hip_fail(e);
+
+    // (3) gate/up GEMM + SiLU*mul
+    {
+        GemmArgs a{};
+        a.M = (int)Rb; a.N = (int)I; a.K = (int)C; a.m_dev = r_dev;
+        a.A0 = xn; a.lda = (int)C; a.a_bytes = (uint32_t)(Rb * C * 2);
+        a.B0 = static_cast<const bf16_t*>(w_gate); a.B1 = static_cast<const bf16_t*>(w_up);
+        a.ldb = (int)C; a.b_bytes = (uint32_t)(I * C * 2);
+        a.pairs = 1; a.splits = 1;
+        a.out0 = H; a.out1 = G; a.out2 = U; a.ldo = (int)I;
+        profile_mark_begin(KC_GEMM_GATE_UP, s);
+        e = launch_gemm(true, true, EPI_SWIGLU, a, s);
+        profile_mark_end(KC_GEMM_GATE_UP, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+
+    // (4) down GEMM + residual scatter-add
+    {
+        GemmArgs a{};
+        a.M = (int)Rb; a.N = (int)C; a.K = (int)I; a.m_dev = r_dev;
+        a.A0 = H; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
+        a.B0 = static_cast<const bf16_t*>(w_down); a.ldb = (int)I; a.b_bytes = (uint32_t)(C * I * 2);
+        a.pairs = 1;
+        const int tiles = (int)((Rb + BM - 1) / BM) * (int)((C + BN - 1) / BN);
+        const int ktiles = (int)((I + BK - 1) / BK);
+        a.splits = choose_splits(tiles, ktiles);
+        a.idx = idx; a.ldo = (int)C;
+        a.no_residual = (flags & SKIPFFN_FLAG_NO_RESIDUAL) ? 1 : 0;
+        profile_mark_begin(KC_GEMM_DOWN, s);
+        if (a.splits == 1) {
+            a.out0 = out; a.e0 = static_cast<const bf16_t*>(hidden);
+            e = launch_gemm(true, true, EPI_RESID_SCATTER, a, s);
+            profile_mark_end(KC_GEMM_DOWN, s);
+            if (e != hipSuccess) return hip_fail(e);
+        } else {
+            a.partial = partial;
+            e = launch_gemm(true, true, EPI_PARTIAL, a, s);
+            profile_mark_end(KC_GEMM_DOWN, s);
+            if (e != hipSuccess) return hip_fail(e);
+            e = launch_resid_scatter(partial, a.splits, (int)Rb, r_dev, (int)C, idx,
+                                     static_cast<const bf16_t*>(hidden), static_cast<bf16_t*>(out),
+                                     a.no_residual, s);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+    }
+    return SKIPFFN_OK;
+}
+
+// ---- backward --------------------------------------------------------------------------------
+int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* grad_out,
+                     void* grad_hidden, const int32_t* idx, int64_t R,
+                     const int32_t* num_retained, const void* rms_gain, const void* w_gate,
+                     const void* w_up, const void* w_down, const void* saved, void* dw_gate,
+                     void* dw_up, void* dw_down, void* workspace, size_t workspace_bytes,
+                     uint32_t flags, void* stream) {
+    int st = check_common(T, C, I, R, num_retained, flags);
+    if (st != SKIPFFN_OK) return st;
+    (void)eps;
+    const int64_t Rb = R < 0 ? T : R;
+    if (T > 0 && (bad_ptr(grad_out) || bad_ptr(grad_hidden))) return SKIPFFN_EINVAL;
+    if (T > 0 && partial_overlap(grad_out, grad_hidden, (size_t)T * C * 2)) return SKIPFFN_EINVAL;
+    if (bad_ptr(dw_gate) || bad_ptr(dw_up) || bad_ptr(dw_down)) return SKIPFFN_EINVAL;
+    if (rms_gain != nullptr && !aligned16(rms_gain)) return SKIPFFN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    const int32_t* r_dev = R < 0 ? num_retained : nullptr;
+    const bool f32 = (flags & SKIPFFN_FLAG_DW_FP32) != 0;
+    const bool accum = (flags & SKIPFFN_FLAG_DW_ACCUMULATE) != 0;
+
+    if (Rb > 0) {
+        if (idx == nullptr || (reinterpret_cast<uintptr_t>(idx) & 3u)) return SKIPFFN_EINVAL;
+        if (bad_ptr(w_gate) || bad_ptr(w_up) || bad_ptr(w_down) || bad_ptr(saved)) return SKIPFFN_EINVAL;
+        BwdWs W = bwd_ws(Rb, C, I);
+        if (workspace == nullptr || !aligned16(workspace)) return SKIPFFN_EWORKSPACE;
+        if (workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
+    }
+
+    hipError_t e;
+    if (T > 0 && grad_hidden != grad_out) {
+        e = launch_passthrough(grad_out, grad_hidden, T, C * 2, idx, (int)Rb, r_dev, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    if (Rb == 0) {
+        if (!accum) {
+            size_t wbytes = (size_t)I * C * (f32 ? 4 : 2);
+            if ((e = launch_fill_zero(dw_gate, wbytes, s)) != hipSuccess) return hip_fail(e);
+            if ((e = launch_fill_zero(dw_up, wbytes, s)) != hipSuccess) return hip_fail(e);
+            if ((e = launch_fill_zero(dw_down, wbytes, s)) != hipSuccess) return hip_fail(e);
+        }
+        return SKIPFFN_OK;
+    }
+    if ((e = ensure_gemm_init()) != hipSuccess) return hip_fail(e);
+
+    SavedLayout L = saved_layout(Rb, C, I);
+    const char* sv = static_cast<const char*>(saved);
+    const bf16_t* xrows = reinterpret_cast<const bf16_t*>(sv + L.off[0]);
+    const bf16_t* xn = reinterpret_cast<const bf16_t*>(sv + L.off[1]);
+    const float* rstd = reinterpret_cast<const float*>(sv + L.off[2]);
+    const bf16_t* G = reinterpret_cast<const bf16_t*>(sv + L.off[3]);
+    const bf16_t* U = reinterpret_cast<const bf16_t*>(sv + L.off[4]);
+    const bf16_t* H = reinterpret_cast<const bf16_t*>(sv + L.off[5]);
+    BwdWs W = bwd_ws(Rb, C, I);
+    char* ws = static_cast<char*>(workspace);
+    bf16_t* dY = reinterpret_cast<bf16_t*>(ws + W.dy);
+    bf16_t* dG = reinterpret_cast<bf16_t*>(ws + W.dg);
+    bf16_t* dU = reinterpret_cast<bf16_t*>(ws + W.du);
+    float* partial = reinterpret_cast<float*>(ws + W.partial);
+
+    // dY = dOut[idx]
+    e = launch_gather_rows(grad_out, dY, C * 2, idx, (int)Rb, r_dev, s);
+    if (e != hipSuccess) return hip_fail(e);
+
+    // dH = dY * W_down, fused with the SiLU*mul backward: dG, dU
+    {
+        GemmArgs a{};
+        a.M = (int)Rb; a.N = (int)I; a.K = (int)C; a.m_dev = r_dev;
+        a.A0 = dY; a.lda = (int)C; a.a_bytes = (uint32_t)(Rb * C * 2);
+        a.B0 = static_cast<const bf16_t*>(w_down); a.ldb = (int)I; a.b_bytes = (uint32_t)(C * I * 2);
+        a.pairs = 1; a.splits = 1;
+        a.out0 = dG; a.out1 = dU; a.ldo = (int)I; a.e0 = G; a.e1 = U; a.lde = (int)I;
+        profile_mark_begin(KC_GEMM_DH, s);
+        e = launch_gemm(true, false, EPI_SWIGLU_BWD, a, s);
+        profile_mark_end(KC_GEMM_DH, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    // dW_down [C, I] = dY^T * H
+    {
+        GemmArgs a{};
+        a.M = (int)C; a.N = (int)I; a.K = (int)Rb; a.k_dev = r_dev;
+        a.A0 = dY; a.lda = (int)C; a.a_bytes = (uint32_t)(Rb * C * 2);
+        a.B0 = H; a.ldb = (int)I; a.b_bytes = (uint32_t)(Rb * I * 2);
+        a.pairs = 1; a.splits = 1;
+        a.out0 = dw_down; a.ldo = (int)I; a.out_f32 = f32; a.accumulate = accum;
+        profile_mark_begin(KC_GEMM_DW_DOWN, s);
+        e = launch_gemm(false, false, EPI_STORE, a, s);
+        profile_mark_end(KC_GEMM_DW_DOWN, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn
+    for (int which = 0; which < 2; ++which) {
+        GemmArgs a{};
+        a.M = (int)I; a.N = (int)C; a.K = (int)Rb; a.k_dev = r_dev;
+        a.A0 = which == 0 ? dG : dU; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
+        a.B0 = xn; a.ldb = (int)C; a.b_bytes = (uint32_t)(Rb * C * 2);
+        a.pairs = 1; a.splits = 1;
+        a.out0 = which == 0 ? dw_gate : dw_up; a.ldo = (int)C; a.out_f32 = f32; a.accumulate = accum;
+        profile_mark_begin(KC_GEMM_DW_GATE_UP, s);
+        e = launch_gemm(false, false, EPI_STORE, a, s);
+        profile_mark_end(KC_GEMM_DW_GATE_UP, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    // dxn = dG * W_gate + dU * W_up  (K runs over both pairs), fp32 split-K slabs
+    int splits;
+    {
+        GemmArgs a{};
+        a.M = (int)Rb; a.N = (int)C; a.K = (int)I; a.m_dev = r_dev;
+        a.A0 = dG; a.A1 = dU; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
+        a.B0 = static_cast<const bf16_t*>(w_gate); a.B1 = static_cast<const bf16_t*>(w_up);
+        a.ldb = (int)C; a.b_bytes = (uint32_t)(I * C * 2);
+        a.pairs = 2;
+        const int tiles = (int)((Rb + BM - 1) / BM) * (int)((C + BN - 1) / BN);
+        const int ktiles = 2 * (int)((I + BK - 1) / BK);
+        a.splits = splits = choose_splits(tiles, ktiles);
+        a.partial = partial;
+        profile_mark_begin(KC_GEMM_DXN, s);
+        e = launch_gemm(true, false, EPI_PARTIAL, a, s);
+        profile_mark_end(KC_GEMM_DXN, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    // RMSNorm backward + residual gradient, scattered to the retained rows
+    e = launch_rmsnorm_bwd_scatter(partial, splits, (int)Rb, r_dev, (int)C, xrows, rstd,
+                                   static_cast<const bf16_t*>(rms_gain), dY, idx,
+                                   static_cast<bf16_t*>(grad_hidden), s);
+    if (e != hipSuccess) return hip_fail(e);
+    return SKIPFFN_OK;
+}
+
+// ---- skip KV-cache row gather -------------------------------------------------------------------
+int skipffn_gather_rows(const void* src, void* dst, int64_t T, int64_t row_bytes,
+                        const int32_t* idx, int64_t R, const int32_t* num_retained, void* stream) {
+    if (T < 0 || row_bytes < 0 || R < -1 || R > T) return SKIPFFN_EINVAL;
+    if (R == -1 && num_retained == nullptr) return SKIPFFN_EINVAL;
+    if (row_bytes & 15) return SKIPFFN_ESHAPE;
+    const int64_t Rb = R < 0 ? T : R;
+    if (Rb == 0 || row_bytes == 0) return SKIPFFN_OK;
+    if (bad_ptr(src) || bad_ptr(dst) || idx == nullptr) return SKIPFFN_EINVAL;
+    if (T > 0x7fffffff) return SKIPFFN_ESHAPE;
+    hipError_t e = launch_gather_rows(src, dst, row_bytes, idx, (int)Rb, R < 0 ? num_retained : nullptr,
+                                      (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,181 @@
+// Mask -> ascending retained-token indices (stream compaction).
+//
+// The retained / skipped partition of Section 4.1 arrives as one byte per token
+// (non-zero = the token skips the FFN).  Each wavefront walks a contiguous token
+// range 256 tokens at a time: a lane loads 4 mask bytes, four wave ballots give
+// the keep-bits of the whole 256-token slab, and mbcnt (popcount of the ballot
+// below the lane) gives every lane its exclusive rank - no shared-memory scan in
+// the inner loop.  Ranges are ordered wave-major inside a block and block-major
+// across blocks, so ranks are ascending in token order and the result is unique
+// and deterministic.  Small inputs (every configuration of the block itself) use
+// one block and one launch; large masks use count / scan / write launches with
+// no spinning between blocks.
+#include "kernels.hpp"
+
+namespace skipffn {
+
+constexpr int CP_THREADS = 1024;
+constexpr int CP_WAVES = CP_THREADS / 64;
+constexpr int64_t CP_SINGLE_MAX = 262144;   // one block up to this many tokens
+constexpr int64_t CP_BLOCK_SPAN = 65536;    // tokens per block beyond that
+
+__device__ __forceinline__ uint32_t load_mask4(const uint8_t* mask, int64_t tok, int64_t end) {
+    // bytes past `end` read as 1 (skipped)
+    if (tok + 4 <= end) return *reinterpret_cast<const uint32_t*>(mask + tok);
+    uint32_t w = 0x01010101u;
+    for (int j = 0; j < 4; ++j)
+        if (tok + j < end) w = (w & ~(0xffu << (8 * j))) | ((uint32_t)mask[tok + j] << (8 * j));
+    return w;
+}
+
+__device__ __forceinline__ int lanes_below(uint64_t m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+
+// number of retained tokens in [begin, end) - one wave
+__device__ int wave_count(const uint8_t* mask, int64_t begin, int64_t end, int lane) {
+    int total = 0;
+    for (int64_t base = begin; base < end; base += 256) {
+        int64_t tok = base + 4 * lane;
+        uint32_t w = tok < end ? load_mask4(mask, tok, end) : 0x01010101u;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            bool keep = ((w >> (8 * j)) & 0xffu) == 0u;
+            total += __popcll(__ballot(keep));
+        }
+    }
+    return total;   // uniform over the wave
+}
+
+__device__ void wave_write(const uint8_t* mask, int64_t begin, int64_t end, int lane,
+                           int out_base, int32_t* idx, int32_t* pos) {
+    for (int64_t base = begin; base < end; base += 256) {
+        int64_t tok = base + 4 * lane;
+        uint32_t w = tok < end ? load_mask4(mask, tok, end) : 0x01010101u;
+        bool keep[4];
+        int rank = 0, slab = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            keep[j] = ((w >> (8 * j)) & 0xffu) == 0u;
+            uint64_t m = __ballot(keep[j]);
+            rank += lanes_below(m);       // kept tokens of lower lanes at byte j
+            slab += __popcll(m);
+        }
+        // tokens of lower lanes at ANY byte position precede this lane's tokens
+        int r = out_base + rank;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (tok + j < end) {
+                if (keep[j]) {
+                    idx[r] = (int32_t)(tok + j);
+                    if (pos) pos[tok + j] = r;
+                    ++r;
+                } else if (pos) {
+                    pos[tok + j] = -1;
+                }
+            }
+        }
+        out_base += slab;
+    }
+}
+
+// MODE 0: single block does everything.  MODE 1: count only -> block_count.
+// MODE 2: write, starting at block_offset[block].
+template <int MODE>
+__global__ __launch_bounds__(CP_THREADS) void compact_kernel(
+    const uint8_t* __restrict__ mask, int64_t T, int64_t span, int32_t* __restrict__ idx,
+    int32_t* __restrict__ num_retained, int32_t* __restrict__ pos,
+    int32_t* __restrict__ block_count, const int32_t* __restrict__ block_offset) {
+    __shared__ int wcount[CP_WAVES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t bbegin = (int64_t)blockIdx.x * span;
+    int64_t bend = bbegin + span < T ? bbegin + span : T;
+    int64_t wspan = span / CP_WAVES;              // multiple of 256 by construction
+    int64_t wbegin = bbegin + wave * wspan;
+    int64_t wend = wbegin + wspan < bend ? wbegin + wspan : bend;
+    if (wbegin > bend) wbegin = bend;
+
+    int c = wave_count(mask, wbegin, wend, lane);
+    if (lane == 0) wcount[wave] = c;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < CP_WAVES; ++w) {
+        int v = wcount[w];
+        before += w < wave ? v : 0;
+        total += v;
+    }
+    if (MODE == 1) {
+        if (threadIdx.x == 0) block_count[blockIdx.x] = total;
+        return;
+    }
+    int base = MODE == 2 ? block_offset[blockIdx.x] : 0;
+    if (MODE == 0 && threadIdx.x == 0) *num_retained = total;
+    wave_write(mask, wbegin, wend, lane, base + before, idx, pos);
+}
+
+// exclusive scan of nb block counts by one block; also writes the grand total
+__global__ __launch_bounds__(CP_THREADS) void compact_scan_kernel(
+    const int32_t* __restrict__ block_count, int nb, int32_t* __restrict__ block_offset,
+    int32_t* __restrict__ num_retained) {
+    __shared__ int part[CP_THREADS];
+    const int t = threadIdx.x;
+    const int per = (nb + CP_THREADS - 1) / CP_THREADS;
+    int lo = t * per, hi = lo + per < nb ? lo + per : nb;
+    int s = 0;
+    for (int i = lo; i < hi; ++i) s += block_count[i];
+    part[t] = s;
+    __syncthreads();
+    // Hillis-Steele inclusive scan over 1024 partial sums
+    for (int off = 1; off < CP_THREADS; off <<= 1) {
+        int v = t >= off ? part[t - off] : 0;
+        __syncthreads();
+        part[t] += v;
+        __syncthreads();
+    }
+    int run = part[t] - s;    // exclusive prefix of this thread's slice
+    for (int i = lo; i < hi; ++i) {
+        block_offset[i] = run;
+        run += block_count[i];
+    }
+    if (t == CP_THREADS - 1) *num_retained = part[t];
+}
+
+static int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+
+static int compact_blocks(int64_t T) {
+    if (T <= CP_SINGLE_MAX) return 1;
+    return (int)((T + CP_BLOCK_SPAN - 1) / CP_BLOCK_SPAN);
+}
+
+size_t compact_workspace_bytes(int64_t T) {
+    int nb = compact_blocks(T < 0 ? 0 : T);
+    return round_up((size_t)nb * 2 * sizeof(int32_t), 256);
+}
+
+hipError_t launch_compact(const uint8_t* mask, int64_t T, int32_t* idx, int32_t* num_retained,
+                          int32_t* pos, void* ws, hipStream_t s) {
+    const int nb = compact_blocks(T);
+    if (nb == 1) {
+        int64_t span = round_up(T > 0 ? T : 1, 256 * CP_WAVES);
+        profile_mark_begin(KC_COMPACT, s);
+        hipLaunchKernelGGL(compact_kernel<0>, dim3(1), dim3(CP_THREADS), 0, s, mask, T, span, idx,
+                           num_retained, pos, (int32_t*)nullptr, (const int32_t*)nullptr);
+        profile_mark_end(KC_COMPACT, s);
+        return hipGetLastError();
+    }
+    int32_t* count = static_cast<int32_t*>(ws);
+    int32_t* offset = count + nb;
+    const int64_t span = CP_BLOCK_SPAN;
+    profile_mark_begin(KC_COMPACT, s);
+    hipLaunchKernelGGL(compact_kernel<1>, dim3(nb), dim3(CP_THREADS), 0, s, mask, T, span, idx,
+                       num_retained, pos, count, (const int32_t*)nullptr);
+    hipLaunchKernelGGL(compact_scan_kernel, dim3(1), dim3(CP_THREADS), 0, s, count, nb, offset,
+                       num_retained);
+    hipLaunchKernelGGL(compact_kernel<2>, dim3(nb), dim3(CP_THREADS), 0, s, mask, T, span, idx,
+                       num_retained, pos, (int32_t*)nullptr, offset);
+    profile_mark_end(KC_COMPACT, s);
+    return hipGetLastError();
+}
+
+}  // namespace skipffn

@@ -1,0 +1,45 @@
+// Instantiations and launcher of the bf16 MFMA GEMM core.
+#include "kernels.hpp"
+
+namespace skipffn {
+
+template <bool A_KC, bool B_KC, int EPI>
+static hipError_t set_lds_limit() {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<A_KC, B_KC, EPI>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+}
+
+hipError_t gemm_init() {
+    hipError_t e;
+    if ((e = set_lds_limit<true, true, EPI_SWIGLU>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_PARTIAL>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<false, false, EPI_STORE>()) != hipSuccess) return e;
+    return hipSuccess;
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
+    const unsigned blocks = (unsigned)(a.tiles_m * a.tiles_n * a.splits);
+    hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI>), dim3(blocks), dim3(GEMM_THREADS),
+                       GEMM_LDS_BYTES, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s) {
+    a.tiles_m = (a.M + BM - 1) / BM;
+    a.tiles_n = (epi == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
+    if (a.splits < 1) a.splits = 1;
+    if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
+    if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU>(a, s);
+    if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL>(a, s);
+    if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER>(a, s);
+    if (a_kc && !b_kc && epi == EPI_SWIGLU_BWD) return launch_one<true, false, EPI_SWIGLU_BWD>(a, s);
+    if (a_kc && !b_kc && epi == EPI_PARTIAL) return launch_one<true, false, EPI_PARTIAL>(a, s);
+    if (!a_kc && !b_kc && epi == EPI_STORE) return launch_one<false, false, EPI_STORE>(a, s);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace skipffn

@@ -1,0 +1,66 @@
+// Host-side launchers of the Skip-FFN kernels.  Every launcher only enqueues
+// work on `stream` and returns the hipError_t of the launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "gemm.hpp"
+
+namespace skipffn {
+
+// kernel classes for the built-in event profiler
+enum KernelClass : int {
+    KC_COMPACT = 0,
+    KC_GATHER_RMSNORM,
+    KC_GEMM_GATE_UP,
+    KC_GEMM_DOWN,
+    KC_RESID_SCATTER,
+    KC_PASSTHROUGH,
+    KC_GATHER_ROWS,
+    KC_GEMM_DH,
+    KC_GEMM_DW_DOWN,
+    KC_GEMM_DW_GATE_UP,
+    KC_GEMM_DXN,
+    KC_RMSNORM_BWD,
+    KC_FILL,
+    KC_COUNT
+};
+const char* kernel_class_name(int kc);
+void profile_mark_begin(int kc, hipStream_t s);
+void profile_mark_end(int kc, hipStream_t s);
+
+// ---- compaction ---------------------------------------------------------------
+size_t compact_workspace_bytes(int64_t T);
+hipError_t launch_compact(const uint8_t* mask, int64_t T, int32_t* idx, int32_t* num_retained,
+                          int32_t* pos, void* ws, hipStream_t s);
+
+// ---- row kernels ---------------------------------------------------------------
+// x rows (optional copy), normalised rows and 1/rms for rows idx[0..R)
+hipError_t launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* idx, int R,
+                                 const int32_t* r_dev, int C, float eps, const bf16_t* gain,
+                                 bf16_t* xrows, bf16_t* xn, float* rstd, hipStream_t s);
+// out[idx[r]] = bf16(res[idx[r]] + sum_z partial[z][r])
+hipError_t launch_resid_scatter(const float* partial, int splits, int R, const int32_t* r_dev,
+                                int C, const int32_t* idx, const bf16_t* res, bf16_t* out,
+                                int no_residual, hipStream_t s);
+// dst[r] = src[idx[r]]  (rows of row_bytes, multiple of 16)
+hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, const int32_t* idx,
+                              int R, const int32_t* r_dev, hipStream_t s);
+// copy every row t of src to dst that is NOT listed in idx (skipped tokens)
+hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row_bytes,
+                              const int32_t* idx, int R, const int32_t* r_dev, hipStream_t s);
+// dX[idx[r]] = bf16(dY[r] + rmsnorm_bwd(sum_z dxn_partial[z][r], x[r], rstd[r], gain))
+hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int R,
+                                      const int32_t* r_dev, int C, const bf16_t* xrows,
+                                      const float* rstd, const bf16_t* gain, const bf16_t* dY,
+                                      const int32_t* idx, bf16_t* dX, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// ---- GEMMs -----------------------------------------------------------------------
+hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation (once per process)
+// layouts: a_kc / b_kc as in gemm.hpp
+hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& args, hipStream_t s);
+
+}  // namespace skipffn

@@ -1,0 +1,313 @@
+// Memory-bound row kernels of the Skip-FFN block: one wavefront per token row,
+// 16-byte accesses, fp32 arithmetic.  Rows are addressed through the retained
+// index list, so only the R retained rows are touched (Section 4.2: skipped
+// tokens keep their residual and see no FFN work).
+#include "kernels.hpp"
+
+namespace skipffn {
+
+constexpr int ROW_THREADS = 256;              // 4 rows per block
+constexpr int ROWS_PER_BLOCK = ROW_THREADS / 64;
+constexpr int RMS_MAXV = 16;                  // register-resident row up to C = 64*8*16 = 8192
+
+__device__ __forceinline__ void unpack8(const u32x4& v, float* f) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f[2 * j] = bf16lo_to_f32(v[j]);
+        f[2 * j + 1] = bf16hi_to_f32(v[j]);
+    }
+}
+__device__ __forceinline__ u32x4 pack8(const float* f) {
+    u32x4 v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = pack_bf16x2(f[2 * j], f[2 * j + 1]);
+    return v;
+}
+
+// ---- gather + RMSNorm -------------------------------------------------------------
+// n(x) = x * rsqrt(mean(x^2) + eps) * gain for the rows idx[r]; x is read once
+// (held in registers), the un-normalised row is optionally copied for backward.
+template <bool IN_REGS>
+__global__ __launch_bounds__(ROW_THREADS) void gather_rmsnorm_kernel(
+    const bf16_t* __restrict__ hidden, const int32_t* __restrict__ idx, int Rbound,
+    const int32_t* __restrict__ r_dev, int C, float eps, const bf16_t* __restrict__ gain,
+    bf16_t* __restrict__ xrows, bf16_t* __restrict__ xn, float* __restrict__ rstd_out) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (r >= R) return;
+    const int chunks = C >> 3;
+    const u32x4* src = reinterpret_cast<const u32x4*>(hidden + (int64_t)idx[r] * C);
+    const u32x4* gsrc = reinterpret_cast<const u32x4*>(gain);
+    u32x4* dxn = reinterpret_cast<u32x4*>(xn + (int64_t)r * C);
+    u32x4* dxr = xrows ? reinterpret_cast<u32x4*>(xrows + (int64_t)r * C) : nullptr;
+
+    u32x4 held[IN_REGS ? RMS_MAXV : 1];
+    float ss = 0.0f;
+    if (IN_REGS) {
+#pragma unroll
+        for (int v = 0; v < RMS_MAXV; ++v) {
+            int c = lane + 64 * v;
+            if (c < chunks) {
+                held[v] = src[c];
+                float f[8];
+                unpack8(held[v], f);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) ss += f[j] * f[j];
+            }
+        }
+    } else {
+        for (int c = lane; c < chunks; c += 64) {
+            float f[8];
+            unpack8(src[c], f);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ss += f[j] * f[j];
+        }
+    }
+    ss = wave_sum(ss);
+    const float rstd = 1.0f / sqrtf(ss / (float)C + eps);
+    if (lane == 0) rstd_out[r] = rstd;
+
+    auto emit = [&](int c, const u32x4& raw) {
+        float f[8];
+        unpack8(raw, f);
+        if (gain != nullptr) {
+            float g[8];
+            unpack8(gsrc[c], g);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) f[j] = f[j] * rstd * g[j];
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) f[j] = f[j] * rstd;
+        }
+        dxn[c] = pack8(f);
+        if (dxr) dxr[c] = raw;
+    };
+    if (IN_REGS) {
+#pragma unroll
+        for (int v = 0; v < RMS_MAXV; ++v) {
+            int c = lane + 64 * v;
+            if (c < chunks) emit(c, held[v]);
+        }
+    } else {
+        for (int c = lane; c < chunks; c += 64) emit(c, src[c]);
+    }
+}
+
+hipError_t launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* idx, int R,
+                                 const int32_t* r_dev, int C, float eps, const bf16_t* gain,
+                                 bf16_t* xrows, bf16_t* xn, float* rstd, hipStream_t s) {
+    if (R <= 0) return hipSuccess;
+    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    profile_mark_begin(KC_GATHER_RMSNORM, s);
+    if (C <= 64 * 8 * RMS_MAXV)
+        hipLaunchKernelGGL(gather_rmsnorm_kernel<true>, grid, block, 0, s, hidden, idx, R, r_dev, C,
+                           eps, gain, xrows, xn, rstd);
+    else
+        hipLaunchKernelGGL(gather_rmsnorm_kernel<false>, grid, block, 0, s, hidden, idx, R, r_dev, C,
+                           eps, gain, xrows, xn, rstd);
+    profile_mark_end(KC_GATHER_RMSNORM, s);
+    return hipGetLastError();
+}
+
+// ---- split-K reduce + residual + scatter ----------------------------------------------
+// out[idx[r]][c] = bf16( res[idx[r]][c] + sum_z partial[z][r][c] ), summed in z order.
+__global__ __launch_bounds__(ROW_THREADS) void resid_scatter_kernel(
+    const float* __restrict__ partial, int splits, int Rbound, const int32_t* __restrict__ r_dev,
+    int C, const int32_t* __restrict__ idx, const bf16_t* res, bf16_t* out, int no_residual) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (r >= R) return;
+    const int chunks = C >> 3;
+    const int64_t orow = (int64_t)idx[r] * C;
+    const int64_t zstride = (int64_t)Rbound * C;
+    for (int c = lane; c < chunks; c += 64) {
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+        const float* p = partial + (int64_t)r * C + c * 8;
+        for (int z = 0; z < splits; ++z) {
+            f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride);
+            f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                acc[j] += a[j];
+                acc[4 + j] += b[j];
+            }
+        }
+        if (!no_residual) {
+            float x[8];
+            unpack8(*reinterpret_cast<const u32x4*>(res + orow + c * 8), x);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += x[j];
+        }
+        *reinterpret_cast<u32x4*>(out + orow + c * 8) = pack8(acc);
+    }
+}
+
+hipError_t launch_resid_scatter(const float* partial, int splits, int R, const int32_t* r_dev,
+                                int C, const int32_t* idx, const bf16_t* res, bf16_t* out,
+                                int no_residual, hipStream_t s) {
+    if (R <= 0) return hipSuccess;
+    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    profile_mark_begin(KC_RESID_SCATTER, s);
+    hipLaunchKernelGGL(resid_scatter_kernel, grid, block, 0, s, partial, splits, R, r_dev, C, idx,
+                       res, out, no_residual);
+    profile_mark_end(KC_RESID_SCATTER, s);
+    return hipGetLastError();
+}
+
+// ---- row gather (upstream gradient rows; skip KV-cache of Section 4.3) -----------------
+__global__ __launch_bounds__(ROW_THREADS) void gather_rows_kernel(
+    const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t row_chunks,
+    const int32_t* __restrict__ idx, int Rbound, const int32_t* __restrict__ r_dev) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (r >= R) return;
+    const u32x4* s = src + (int64_t)idx[r] * row_chunks;
+    u32x4* d = dst + (int64_t)r * row_chunks;
+    for (int64_t c = lane; c < row_chunks; c += 64) d[c] = s[c];
+}
+
+hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, const int32_t* idx,
+                              int R, const int32_t* r_dev, hipStream_t s) {
+    if (R <= 0 || row_bytes <= 0) return hipSuccess;
+    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    profile_mark_begin(KC_GATHER_ROWS, s);
+    hipLaunchKernelGGL(gather_rows_kernel, grid, block, 0, s, static_cast<const u32x4*>(src),
+                       static_cast<u32x4*>(dst), row_bytes / 16, idx, R, r_dev);
+    profile_mark_end(KC_GATHER_ROWS, s);
+    return hipGetLastError();
+}
+
+// ---- bit copy of skipped rows (out-of-place calls) ---------------------------------------
+// A row t is copied unless a binary search finds it in the ascending list idx.
+__global__ __launch_bounds__(ROW_THREADS) void passthrough_kernel(
+    const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t T, int64_t row_chunks,
+    const int32_t* __restrict__ idx, int Rbound, const int32_t* __restrict__ r_dev) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int lane = threadIdx.x & 63;
+    const int64_t t = (int64_t)blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (t >= T) return;
+    int lo = 0, hi = R;              // first position with idx[pos] >= t
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (idx[mid] < t) lo = mid + 1; else hi = mid;
+    }
+    if (lo < R && idx[lo] == t) return;   // retained: written by the scatter epilogue
+    const u32x4* s = src + t * row_chunks;
+    u32x4* d = dst + t * row_chunks;
+    for (int64_t c = lane; c < row_chunks; c += 64) d[c] = s[c];
+}
+
+hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row_bytes,
+                              const int32_t* idx, int R, const int32_t* r_dev, hipStream_t s) {
+    if (T <= 0 || row_bytes <= 0) return hipSuccess;
+    dim3 grid((unsigned)((T + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK)), block(ROW_THREADS);
+    profile_mark_begin(KC_PASSTHROUGH, s);
+    hipLaunchKernelGGL(passthrough_kernel, grid, block, 0, s, static_cast<const u32x4*>(src),
+                       static_cast<u32x4*>(dst), T, row_bytes / 16, idx, R < 0 ? 0 : R, r_dev);
+    profile_mark_end(KC_PASSTHROUGH, s);
+    return hipGetLastError();
+}
+
+// ---- RMSNorm backward + residual gradient + scatter ----------------------------------------
+// With xh = x * rstd and dxh = dxn * gain:
+//   dx = rstd * (dxh - xh * mean_c(dxh * xh));  dX[idx[r]] = bf16(dY[r] + dx)
+// dxn arrives as `splits` fp32 partial sums [z][r][c] (the split-K slabs of the
+// dG*W_gate + dU*W_up GEMM), added here in z order.
+__global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
+    const float* __restrict__ part, int splits, int Rbound, const int32_t* __restrict__ r_dev,
+    int C, const bf16_t* __restrict__ xrows, const float* __restrict__ rstd_in,
+    const bf16_t* __restrict__ gain, const bf16_t* __restrict__ dY,
+    const int32_t* __restrict__ idx, bf16_t* dX) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
+    if (r >= R) return;
+    const int chunks = C >> 3;
+    const float rstd = rstd_in[r];
+    const int64_t zstride = (int64_t)Rbound * C;
+    const float* p = part + (int64_t)r * C;
+    const u32x4* xs = reinterpret_cast<const u32x4*>(xrows + (int64_t)r * C);
+    const u32x4* gs = reinterpret_cast<const u32x4*>(gain);
+
+    auto load_dxh = [&](int c, float* d) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) d[j] = 0.0f;
+        for (int z = 0; z < splits; ++z) {
+            f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride + c * 8);
+            f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + c * 8 + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                d[j] += a[j];
+                d[4 + j] += b[j];
+            }
+        }
+        if (gain != nullptr) {
+            float g[8];
+            unpack8(gs[c], g);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) d[j] *= g[j];
+        }
+    };
+
+    float dot = 0.0f;
+    for (int c = lane; c < chunks; c += 64) {
+        float d[8], x[8];
+        load_dxh(c, d);
+        unpack8(xs[c], x);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dot += d[j] * (x[j] * rstd);
+    }
+    dot = wave_sum(dot) / (float)C;
+
+    const u32x4* dys = reinterpret_cast<const u32x4*>(dY + (int64_t)r * C);
+    u32x4* out = reinterpret_cast<u32x4*>(dX + (int64_t)idx[r] * C);
+    for (int c = lane; c < chunks; c += 64) {
+        float d[8], x[8], gy[8], o[8];
+        load_dxh(c, d);
+        unpack8(xs[c], x);
+        unpack8(dys[c], gy);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = gy[j] + rstd * (d[j] - (x[j] * rstd) * dot);
+        out[c] = pack8(o);
+    }
+}
+
+hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int R,
+                                      const int32_t* r_dev, int C, const bf16_t* xrows,
+                                      const float* rstd, const bf16_t* gain, const bf16_t* dY,
+                                      const int32_t* idx, bf16_t* dX, hipStream_t s) {
+    if (R <= 0) return hipSuccess;
+    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    profile_mark_begin(KC_RMSNORM_BWD, s);
+    hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel, grid, block, 0, s, dxn_partial, splits, R, r_dev,
+                       C, xrows, rstd, gain, dY, idx, dX);
+    profile_mark_end(KC_RMSNORM_BWD, s);
+    return hipGetLastError();
+}
+
+// ---- zero fill (a kernel, so that it can be captured in a HIP graph) -----------------------
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* p, size_t chunks) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * 256;
+    u32x4 z = {0u, 0u, 0u, 0u};
+    for (; i < chunks; i += stride) p[i] = z;
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return hipSuccess;
+    size_t chunks = bytes / 16;     // callers pass multiples of 16
+    size_t blocks = (chunks + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    profile_mark_begin(KC_FILL, s);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                       static_cast<u32x4*>(p), chunks);
+    profile_mark_end(KC_FILL, s);
+    return hipGetLastError();
+}
+
+}  // namespace skipffn

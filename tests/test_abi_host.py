@@ -1,0 +1,123 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every declared symbol, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2503_21817_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "skipffn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(skipffn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = declared_symbols()
+    assert len(names) >= 14
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.exported_symbols()) == names
+    assert B.skipffn_version() >= 100
+
+
+def test_status_strings():
+    lib = B.lib()
+    seen = {lib.skipffn_status_string(i).decode() for i in range(6)}
+    assert len(seen) == 6
+    assert "unknown" in lib.skipffn_status_string(99).decode()
+
+
+def test_size_queries_are_monotone_and_cover_their_sections():
+    C, I = 4096, 14336
+    for R in (0, 1, 255, 1472, 2560):
+        sv = B.skipffn_saved_bytes(R, C, I)
+        off = B.skipffn_saved_layout(R, C, I)
+        assert off == sorted(off) and off[0] == 0
+        assert sv >= off[5] + R * I * 2
+        assert off[1] - off[0] >= R * C * 2 and off[3] - off[2] >= R * 4
+        fw_inf = B.skipffn_forward_workspace_bytes(R, C, I, False)
+        fw_tr = B.skipffn_forward_workspace_bytes(R, C, I, True)
+        assert fw_inf >= fw_tr >= R * C * 4
+        assert B.skipffn_backward_workspace_bytes(R, C, I) >= R * C * 2 + 2 * R * I * 2
+    assert B.skipffn_saved_bytes(2560, C, I) > B.skipffn_saved_bytes(1472, C, I)
+    assert B.skipffn_compact_workspace_bytes(0) > 0
+    assert B.skipffn_compact_workspace_bytes(1 << 26) >= 2 * 4 * ((1 << 26) // 65536)
+
+
+FAKE = 0x7f0000001000      # aligned, never dereferenced: validation fails first
+ODD = FAKE + 2
+
+
+def fwd(T=8, C=64, I=128, eps=1e-5, hidden=FAKE, out=FAKE, idx=FAKE, R=4, nr=None, gain=None,
+        wg=FAKE, wu=FAKE, wd=FAKE, saved=None, ws=FAKE, ws_bytes=1 << 40, flags=0):
+    return B.lib().skipffn_forward(T, C, I, eps, hidden, out, idx, R, nr, gain, wg, wu, wd, saved,
+                                   ws, ws_bytes, flags, None)
+
+
+def bwd(T=8, C=64, I=128, go=FAKE, gh=FAKE, idx=FAKE, R=4, nr=None, wg=FAKE, wu=FAKE, wd=FAKE,
+        saved=FAKE, dwg=FAKE, dwu=FAKE, dwd=FAKE, ws=FAKE, ws_bytes=1 << 40, flags=0):
+    return B.lib().skipffn_backward(T, C, I, 1e-5, go, gh, idx, R, nr, None, wg, wu, wd, saved,
+                                    dwg, dwu, dwd, ws, ws_bytes, flags, None)
+
+
+def test_forward_rejects_bad_arguments_on_the_host():
+    assert fwd(T=-1) == B.EINVAL
+    assert fwd(R=9) == B.EINVAL                 # R > T
+    assert fwd(R=-1, nr=None) == B.EINVAL       # device count requested, no pointer
+    assert fwd(R=-2) == B.EINVAL
+    assert fwd(C=60) == B.ESHAPE
+    assert fwd(I=100) == B.ESHAPE
+    assert fwd(T=1 << 20, C=4096, R=4) == B.ESHAPE      # hidden >= 2 GiB
+    assert fwd(hidden=None) == B.EINVAL
+    assert fwd(hidden=ODD) == B.EINVAL
+    assert fwd(out=FAKE + 16) == B.EINVAL       # partial overlap
+    assert fwd(idx=None) == B.EINVAL
+    assert fwd(wg=None) == B.EINVAL
+    assert fwd(wd=ODD) == B.EINVAL
+    assert fwd(gain=ODD) == B.EINVAL
+    assert fwd(flags=0x100) == B.EUNSUPPORTED
+    assert fwd(ws=None) == B.EWORKSPACE
+    assert fwd(ws_bytes=16) == B.EWORKSPACE
+    assert fwd(eps=float("nan")) == B.EINVAL
+    # T == 0 and R == 0 in place are valid no-ops that enqueue nothing
+    assert fwd(T=0, R=0, hidden=None, out=None, idx=None, ws=None, ws_bytes=0) == B.OK
+    assert fwd(R=0, idx=None, ws=None, ws_bytes=0) == B.OK
+
+
+def test_backward_rejects_bad_arguments_on_the_host():
+    assert bwd(T=-1) == B.EINVAL
+    assert bwd(R=9) == B.EINVAL
+    assert bwd(C=60) == B.ESHAPE
+    assert bwd(go=None) == B.EINVAL
+    assert bwd(gh=FAKE + 32) == B.EINVAL
+    assert bwd(saved=None) == B.EINVAL
+    assert bwd(dwg=None) == B.EINVAL
+    assert bwd(dwd=ODD) == B.EINVAL
+    assert bwd(flags=0x8) == B.EUNSUPPORTED
+    assert bwd(ws_bytes=0) == B.EWORKSPACE
+
+
+def test_compact_and_gather_reject_bad_arguments_on_the_host():
+    lib = B.lib()
+    assert lib.skipffn_compact(FAKE, -1, FAKE, FAKE, None, FAKE, 1 << 20, None) == B.EINVAL
+    assert lib.skipffn_compact(FAKE, 10, FAKE, None, None, FAKE, 1 << 20, None) == B.EINVAL
+    assert lib.skipffn_compact(ODD, 10, FAKE, FAKE, None, FAKE, 1 << 20, None) == B.EINVAL
+    assert lib.skipffn_compact(FAKE, 10, FAKE, FAKE, None, FAKE, 0, None) == B.EWORKSPACE
+    assert lib.skipffn_gather_rows(FAKE, FAKE, 10, 24, FAKE, 3, None, None) == B.ESHAPE
+    assert lib.skipffn_gather_rows(FAKE, FAKE, 10, 32, FAKE, 11, None, None) == B.EINVAL
+    assert lib.skipffn_gather_rows(None, FAKE, 10, 32, FAKE, 3, None, None) == B.EINVAL
+    assert lib.skipffn_gather_rows(FAKE, FAKE, 10, 32, FAKE, 0, None, None) == B.OK
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        B.lib()

@@ -1,0 +1,233 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Integer / byte results are compared bit for bit;
+floating-point results by relative L2 error over retained rows, bound 1e-2
+(bf16 inputs, fp32 accumulation, bf16 intermediates)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import skipffn_oracle as O
+from paper_2503_21817_amd import binding as B
+from paper_2503_21817_amd import workloads as W
+from helpers import REL_L2_TOL, Problem, bits_of, f64_of, rel_l2, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def run_compact(mask_np, want_pos=True):
+    T = mask_np.shape[0]
+    d_mask = torch.from_numpy(mask_np).cuda() if T else torch.empty(0, dtype=torch.uint8, device="cuda")
+    idx = torch.full((max(T, 1),), -7, dtype=torch.int32, device="cuda")
+    nr = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    pos = torch.full((max(T, 1),), -7, dtype=torch.int32, device="cuda") if want_pos else None
+    ws = torch.empty(max(B.skipffn_compact_workspace_bytes(T), 16), dtype=torch.uint8, device="cuda")
+    B.skipffn_compact(d_mask, idx, nr, pos, ws)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), int(nr.item()), None if pos is None else pos.cpu().numpy()
+
+
+@pytest.mark.parametrize("T", [0, 1, 3, 64, 255, 256, 257, 1000, 4097, 16384, 29411, 262144,
+                               262145, 300001, (1 << 20) + 37])
+@pytest.mark.parametrize("kind", ["rand", "all0", "all1", "alt", "ends", "bytes"])
+def test_compact_bit_exact(T, kind):
+    rng = np.random.default_rng(T + len(kind))
+    if kind == "rand":
+        m = (rng.random(T) < 0.7).astype(np.uint8)
+    elif kind == "all0":
+        m = np.zeros(T, np.uint8)
+    elif kind == "all1":
+        m = np.ones(T, np.uint8)
+    elif kind == "alt":
+        m = (np.arange(T) % 2).astype(np.uint8)
+    elif kind == "ends":
+        m = np.ones(T, np.uint8); m[:1] = 0; m[-1:] = 0
+    else:
+        m = (rng.integers(0, 256, T) * (rng.random(T) < 0.5)).astype(np.uint8)
+    print(f"compact T={T} kind={kind}", flush=True)
+    idx, R, pos = run_compact(m)
+    oidx, oR, opos = O.compact(m)
+    assert R == oR
+    assert np.array_equal(idx[:R], oidx)
+    if T:
+        assert np.all(idx[R:T] == -7)          # entries beyond R untouched
+        assert np.array_equal(pos[:T], opos)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_compact_on_workload_masks(cfg):
+    w = W.config(cfg)
+    m = W.make_mask(w)
+    idx, R, pos = run_compact(m, want_pos=False)
+    oidx, oR, _ = O.compact(m)
+    assert R == oR == w.R and np.array_equal(idx[:R], oidx)
+
+
+def gpu_forward(p, R_host=True, inplace=False, saved=True, flags=0):
+    w = p.w
+    bufs = B.SkipFFNBuffers(w.T, w.T if not R_host else w.R, w.C, w.I, training=saved)
+    B.skipffn_compact(p.d_mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+    hidden = p.d_hidden.clone()
+    out = hidden if inplace else torch.full_like(hidden, float("nan"))
+    B.skipffn_forward(hidden, out, bufs.idx, w.R if R_host else None, p.d_wg, p.d_wu, p.d_wd,
+                      eps=w.eps, rms_gain=p.d_gain, num_retained=bufs.num_retained,
+                      saved=bufs.saved, workspace=bufs.fwd_ws, flags=flags)
+    torch.cuda.synchronize()
+    return out, bufs
+
+
+def gpu_backward(p, bufs, R_host=True, inplace=False, flags=0, dw=None):
+    w = p.w
+    grad = p.d_grad.clone()
+    gh = grad if inplace else torch.full_like(grad, float("nan"))
+    dt = torch.float32 if flags & B.FLAG_DW_FP32 else torch.bfloat16
+    if dw is None:
+        dw = [torch.full((w.I, w.C), float("nan"), dtype=dt, device="cuda"),
+              torch.full((w.I, w.C), float("nan"), dtype=dt, device="cuda"),
+              torch.full((w.C, w.I), float("nan"), dtype=dt, device="cuda")]
+    B.skipffn_backward(grad, gh, bufs.idx, w.R if R_host else None, p.d_wg, p.d_wu, p.d_wd,
+                       bufs.saved, dw[0], dw[1], dw[2], eps=w.eps, rms_gain=p.d_gain,
+                       num_retained=bufs.num_retained, workspace=bufs.bwd_ws, flags=flags)
+    torch.cuda.synchronize()
+    return gh, dw
+
+
+SMALL = [
+    W.config(1),
+    W.small(C=512, I=1368, visual=(300, 411), text=(20, 35), keep=(130, 212), seed=11, name="ragged-2tiles"),
+    W.small(C=264, I=520, visual=(700,), text=(9,), keep=(600,), seed=12, name="odd-dims-3tiles"),
+    W.small(C=1024, I=2048, visual=(64,), text=(1,), keep=(0,), seed=13, name="one-row"),
+]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("gain", [False, True])
+def test_forward_stage_by_stage(w, gain):
+    print(f"forward stages {w.name} T={w.T} R={w.R} C={w.C} I={w.I} gain={gain}", flush=True)
+    p = Problem(w, unit_gain=not gain, with_gain_tensor=gain)
+    ref = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps)
+    out, bufs = gpu_forward(p)
+    R = w.R
+    idx = bufs.idx[:R].cpu().numpy()
+    assert np.array_equal(idx, ref["idx"])
+    sv = bufs.saved_views(R)
+    # gathered input rows are bit copies
+    assert np.array_equal(bits_of(sv["xrows"]), p.hidden[idx])
+    assert rel_l2(f64_of(sv["rstd"]), ref["rstd"]) < 1e-6
+    assert rel_l2(f64_of(sv["xn"]), ref["xn"]) < 3e-3          # one bf16 rounding: 2^-9 rms
+    for k in ("G", "U", "H"):
+        assert rel_l2(f64_of(sv[k]), ref[k]) < REL_L2_TOL, k
+    got = bits_of(out)
+    skipped = p.mask != 0
+    assert np.array_equal(got[skipped], p.hidden[skipped])      # bitwise passthrough
+    e = rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(ref["out_bits"][idx]))
+    assert e < REL_L2_TOL, e
+    # the FFN update on its own (the residual can hide it when |y| << |x|)
+    y_out, _ = gpu_forward(p, flags=B.FLAG_NO_RESIDUAL)
+    yb = bits_of(y_out)
+    assert np.array_equal(yb[skipped], p.hidden[skipped])
+    ey = rel_l2(O.bf16_bits_to_f64(yb[idx]), ref["Y"])
+    assert ey < REL_L2_TOL, ey
+
+
+@pytest.mark.parametrize("w", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("gain", [False, True])
+def test_backward_against_oracle(w, gain):
+    print(f"backward {w.name} T={w.T} R={w.R} C={w.C} I={w.I} gain={gain}", flush=True)
+    p = Problem(w, unit_gain=not gain, with_gain_tensor=gain)
+    ref = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    _, bufs = gpu_forward(p)
+    gh, dw = gpu_backward(p, bufs)
+    idx = ref["idx"]
+    got = bits_of(gh)
+    skipped = p.mask != 0
+    assert np.array_equal(got[skipped], p.grad[skipped])
+    e = rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(ref["dx_bits"][idx]))
+    assert e < REL_L2_TOL, ("dx", e)
+    for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+        e = rel_l2(f64_of(t), ref[k])
+        assert e < REL_L2_TOL, (k, e)
+    # fp32 weight gradients, then accumulation on top of them: 2x
+    gh32, dw32 = gpu_backward(p, bufs, flags=B.FLAG_DW_FP32)
+    assert np.array_equal(bits_of(gh32), got)
+    for t, k in zip(dw32, ("dw_gate", "dw_up", "dw_down")):
+        assert rel_l2(f64_of(t), ref[k]) < REL_L2_TOL, k
+    first = [t.clone() for t in dw32]
+    gpu_backward(p, bufs, flags=B.FLAG_DW_FP32 | B.FLAG_DW_ACCUMULATE, dw=dw32)
+    for t, f in zip(dw32, first):
+        assert torch.equal(t, 2 * f)
+    # bf16 accumulate onto zeros equals overwrite
+    z = [torch.zeros_like(t) for t in dw]
+    gpu_backward(p, bufs, flags=B.FLAG_DW_ACCUMULATE, dw=z)
+    for t, f in zip(z, dw):
+        assert torch.equal(t, f)
+
+
+def test_invariants_on_gpu():
+    w = W.small(C=512, I=1024, visual=(300,), text=(30,), keep=(77,), seed=21)
+    p = Problem(w)
+    out1, bufs = gpu_forward(p)
+    # run twice: bitwise equal (deterministic reduction order)
+    out2, _ = gpu_forward(p)
+    assert torch.equal(out1.view(torch.int16), out2.view(torch.int16))
+    # in place == out of place
+    out3, _ = gpu_forward(p, inplace=True)
+    assert torch.equal(out1.view(torch.int16), out3.view(torch.int16))
+    # device-side R == host R
+    out4, bufs4 = gpu_forward(p, R_host=False)
+    assert torch.equal(out1.view(torch.int16), out4.view(torch.int16))
+    gh1, dw1 = gpu_backward(p, bufs)
+    gh2, dw2 = gpu_backward(p, bufs, inplace=True)
+    gh4, dw4 = gpu_backward(p, bufs4, R_host=False)
+    assert torch.equal(gh1.view(torch.int16), gh2.view(torch.int16))
+    assert torch.equal(gh1.view(torch.int16), gh4.view(torch.int16))
+    for a, b, c in zip(dw1, dw2, dw4):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+        assert torch.equal(a.view(torch.int16), c.view(torch.int16))
+
+
+def test_retain_all_and_retain_none():
+    base = W.small(C=256, I=512, visual=(150,), text=(10,), keep=(150,), seed=31)
+    p = Problem(base)
+    assert not p.mask.any()
+    out, bufs = gpu_forward(p)
+    wide = [O.bf16_bits_to_f64(a) for a in (p.hidden, p.wg, p.wu, p.wd)]
+    dense = O.dense_swiglu_layer(wide[0], wide[1], wide[2], wide[3], None, base.eps)
+    assert rel_l2(f64_of(out), dense) < REL_L2_TOL
+    none = W.small(C=256, I=512, visual=(150,), text=(0,), keep=(0,), seed=32)
+    q = Problem(none)
+    q.hidden[3, :4] = [0x7FC1, 0xFF80, 0x8000, 0x0001]
+    q.d_hidden = to_dev_bf16(q.hidden)
+    assert q.mask.all()
+    out, bufs = gpu_forward(q)
+    assert np.array_equal(bits_of(out), q.hidden)
+    assert int(bufs.num_retained.item()) == 0
+    gh, dw = gpu_backward(q, bufs)
+    assert np.array_equal(bits_of(gh), q.grad)
+    for t in dw:
+        assert not t.view(torch.int16).any()
+    # accumulate with R == 0 leaves dW alone
+    keep = [torch.ones_like(t) for t in dw]
+    gpu_backward(q, bufs, flags=B.FLAG_DW_ACCUMULATE, dw=keep)
+    for t in keep:
+        assert torch.equal(t, torch.ones_like(t))
+
+
+def test_inference_forward_without_saved_buffer():
+    w = W.small(C=512, I=1024, visual=(300,), text=(30,), keep=(77,), seed=21)
+    p = Problem(w)
+    a, _ = gpu_forward(p, saved=True)
+    b, _ = gpu_forward(p, saved=False)
+    assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def test_skip_kv_cache_row_gather():
+    rng = np.random.default_rng(5)
+    T, D = 777, 1024
+    cache = rng.integers(0, 65536, (T, D)).astype(np.uint16)
+    m = (rng.random(T) < 0.75).astype(np.uint8)
+    idx, R, _ = O.compact(m)
+    src = to_dev_bf16(cache)
+    dst = torch.zeros((R, D), dtype=torch.bfloat16, device="cuda")
+    B.skipffn_gather_rows(src, dst, torch.from_numpy(idx).cuda(), R)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(dst), O.kv_skip_cache(cache, m))
