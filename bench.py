@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the Skip-FFN block on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic batch: mask
+compaction, gather + RMSNorm, gate/up GEMM + SiLU*mul, down GEMM + residual
+scatter, and the backward over retained rows (dX, dW_gate, dW_up, dW_down).
+Inputs are resident in HBM before the timed region starts.  One JSON line is
+printed (see README for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--passes fwd+bwd]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..4 (token mix and layer shape)")
+    ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
+    return ap.parse_args()
+
+
+def kernel_work(name, R, T, C, I, dw_bytes):
+    """(kind, algorithmic amount per launch): flops for the MFMA kernels, bytes for
+    the HBM-bound ones."""
+    rc, ri = R * C, R * I
+    table = {
+        "gemm_gate_up_swiglu": ("mfma", 4 * R * C * I),
+        "gemm_down": ("mfma", 2 * R * C * I),
+        "gemm_dh_swiglu_bwd": ("mfma", 2 * R * C * I),
+        "gemm_dw_down": ("mfma", 2 * R * C * I),
+        "gemm_dw_gate_up": ("mfma", 2 * R * C * I),
+        "gemm_dxn": ("mfma", 4 * R * C * I),
+        "compact": ("hbm", T + 4 * R),
+        "gather_rmsnorm": ("hbm", 2 * rc * 2 + 4 * R),
+        "resid_scatter": ("hbm", 2 * rc * 2),
+        "gather_rows": ("hbm", 2 * rc * 2),
+        "rmsnorm_bwd_scatter": ("hbm", rc * (2 + 2 + 4 + 2)),
+        "passthrough_copy": ("hbm", 2 * (T - R) * C * 2),
+    }
+    return table.get(name, ("hbm", 0))
+
+
+def cpu_baseline(w, passes, target_s):
+    """The oracle, as it stands, on a bounded sample of the same workload: the
+    first sequences of the batch (all of their tokens), sized for ~target_s."""
+    from oracle import skipffn_oracle as O
+    from paper_2503_21817_amd import workloads as W
+    from paper_2503_21817_amd.flopmodel import skipffn_flops
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    mask, hidden, grad = W.make_mask(w), W.make_hidden(w), W.make_grad(w)
+    wg, wu, wd = W.make_weights(w)
+    lens = [v + t for v, t in zip(w.visual, w.text)]
+
+    def run(nseq):
+        n = sum(lens[:nseq])
+        t0 = time.perf_counter()
+        O.skipffn_forward(hidden[:n], mask[:n], wg, wu, wd, None, w.eps)
+        if passes == "fwd+bwd":
+            O.skipffn_backward(hidden[:n], mask[:n], wg, wu, wd, grad[:n], None, w.eps)
+        dt = time.perf_counter() - t0
+        R = int((mask[:n] == 0).sum())
+        return dt, n, R
+
+    dt1, n1, R1 = run(1)
+    nseq = 1
+    if len(lens) > 1 and dt1 < target_s / 2:
+        nseq = int(min(len(lens), max(1, target_s // max(dt1, 1e-3))))
+    dt, n, R = (dt1, n1, R1) if nseq == 1 else run(nseq)
+    flops = skipffn_flops(R, w.C, w.I, passes == "fwd+bwd")
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {nseq} of {len(lens)} sequences ({n} tokens, {R} retained), "
+                      f"{passes}, fp64 numpy, {dt:.1f} s",
+            "seconds": dt, "retained_tokens_per_s": R / dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the Skip-FFN block of one data-parallel rank); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2503_21817_amd import binding as B
+    from paper_2503_21817_amd import workloads as W
+    from paper_2503_21817_amd.flopmodel import skipffn_flops
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()   # fail loudly if the HIP library is missing
+
+    w = W.config(args.config)
+    bwd = args.passes == "fwd+bwd"
+    T, R, C, I = w.T, w.R, w.C, w.I
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    mask = torch.from_numpy(W.make_mask(w)).cuda()
+    hidden0 = dev_bf16(W.make_hidden(w))
+    grad0 = dev_bf16(W.make_grad(w))
+    wg, wu, wd = (dev_bf16(a) for a in W.make_weights(w))
+    bufs = B.SkipFFNBuffers(T, R, C, I, training=bwd)
+    dwg = torch.empty((I, C), dtype=torch.bfloat16, device="cuda")
+    dwu = torch.empty((I, C), dtype=torch.bfloat16, device="cuda")
+    dwd = torch.empty((C, I), dtype=torch.bfloat16, device="cuda")
+
+    # The block runs in place (skipped rows are never touched); rotate through
+    # fresh copies of the input so values do not drift from step to step.
+    ncopy = min(args.steps + args.warmup, 32)
+    hiddens = [hidden0.clone() for _ in range(ncopy)]
+    grads = [grad0.clone() for _ in range(ncopy)] if bwd else []
+
+    def step(i):
+        h = hiddens[i % ncopy]
+        B.skipffn_compact(mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+        B.skipffn_forward(h, h, bufs.idx, R, wg, wu, wd, eps=w.eps, saved=bufs.saved,
+                          workspace=bufs.fwd_ws)
+        if bwd:
+            g = grads[i % ncopy]
+            B.skipffn_backward(g, g, bufs.idx, R, wg, wu, wd, bufs.saved, dwg, dwu, dwd,
+                               eps=w.eps, workspace=bufs.bwd_ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / args.steps * 1e3
+
+    # Per-kernel durations: HIP events recorded by the library around every
+    # launch, on the stream the kernels run on, over the same K steps.
+    for i in range(ncopy):
+        hiddens[i].copy_(hidden0)
+        if bwd:
+            grads[i].copy_(grad0)
+    torch.cuda.synchronize()
+    B.skipffn_profile_begin()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    torch.cuda.synchronize()
+    ms_step_prof = (time.perf_counter() - t0) / args.steps * 1e3
+    prof = B.skipffn_profile_end()
+
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        kind, amount = kernel_work(name, R, T, C, I, 2)
+        avg = ms / n
+        e = {"avg_ms": round(avg, 5), "launches_per_step": n / args.steps}
+        if amount and avg > 0:
+            if kind == "mfma":
+                e["tflops"] = round(amount / (avg * 1e-3) / 1e12, 1)
+                e["frac_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+            else:
+                e["gbs"] = round(amount / (avg * 1e-3) / 1e9, 1)
+                e["frac_peak"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        e["ms_per_step"] = round(ms / args.steps, 5)
+        kernels[name] = e
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    kind, amount = kernel_work(dom, R, T, C, I, 2)
+    dom_avg_s = kernels[dom]["avg_ms"] * 1e-3
+    if kind == "mfma":
+        achieved, peak, unit = amount / dom_avg_s / 1e12, PEAK_BF16_TFLOPS, "TFLOP/s"
+    else:
+        achieved, peak, unit = amount / dom_avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
+    roofline = {"kernel": dom, "bound": kind, "achieved": round(achieved, 2), "peak": peak,
+                "unit": unit, "frac": round(achieved / peak, 4), "traffic": None,
+                "avg_launch_ms": kernels[dom]["avg_ms"]}
+    gemm_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k.startswith("gemm_"))
+
+    flops = skipffn_flops(R, C, I, bwd)
+    tflops = flops / (ms_step * 1e-3) / 1e12
+    rec = {
+        "metric": "retained-token FFN fwd+bwd TFLOP/s" if bwd else "retained-token FFN fwd TFLOP/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: T={T} tokens, R={R} retained, C={C}, I={I}, "
+                               f"1 layer, {args.passes}, in place",
+                   "T": T, "R": R, "C": C, "I": I, "passes": args.passes},
+        "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "gemm_only_tflops": round(flops / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms > 0 else None,
+        "effective_tokens_per_s": round(T / (ms_step * 1e-3)),
+        "retained_tokens_per_s": round(R / (ms_step * 1e-3)),
+        "ms_per_step_with_events": round(ms_step_prof, 4),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(w, args.passes, args.cpu_seconds)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()
