@@ -1,7 +1,7 @@
 // bf16 MFMA GEMM core for gfx950 with the fused epilogues of the Skip-FFN block.
 //
 // One workgroup = 512 threads = 8 wavefronts (2 per SIMD) computes a 256 x 256
-// tile of C = A * B with fp32 accumulation, stepping K in slabs of 32.  Waves
+// tile of C = A * B with fp32 accumulation, stepping K in slabs of 64.  Waves
 // are arranged 2 (M) x 4 (N); each owns 128 x 64 = 4 x 2 MFMA tiles of
 // v_mfma_f32_32x32x16_bf16 (128 accumulator registers).
 //
@@ -15,11 +15,13 @@
 // column.  XOR swizzles, applied on the global-address side of the direct loads,
 // keep both read patterns free of LDS bank conflicts.
 //
-// LDS holds a ring of NSTAGE = 5 slabs (5 x 32 KB = all 160 KB of the CU), up to
-// four of them in flight from memory, so memory latency of about three slab times
-// is covered.  The two waves of each SIMD alternate between a memory phase and a
-// compute phase half a slab apart (see the main loop), which keeps the matrix
-// pipe fed while fragments are read and loads are issued.
+// LDS (160 KB) holds a ring of 2 A slabs and 3 B slabs of 256 x 64 (32 KB each):
+// B is the operand that streams from HBM in every GEMM of the block (weights, or
+// the long activation matrix), so it is fetched two slabs ahead, A one slab ahead.
+// A slab row of a KC operand is one full 128-byte line, which keeps the address
+// unit at one line per 8 lanes.  The two waves of each SIMD alternate between a
+// memory phase and a compute phase half a slab apart (see the main loop), which
+// keeps the matrix pipe fed while fragments are read and loads are issued.
 //
 // Global loads are raw buffer loads: lanes outside the matrix (ragged M, K or N
 // tails) read zeros, so no shape restriction beyond "dimensions are multiples
@@ -30,12 +32,12 @@
 
 namespace skipffn {
 
-constexpr int BM = 256, BN = 256, BK = 32;
+constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 512;
-constexpr int NSTAGE = 5;
-constexpr int OPER_BYTES = BM * BK * 2;             // 16 KB per operand per stage
-constexpr int STAGE_BYTES = 2 * OPER_BYTES;         // 32 KB
-constexpr int GEMM_LDS_BYTES = NSTAGE * STAGE_BYTES;  // 160 KB
+constexpr int NSTAGE_A = 2, NSTAGE_B = 3;
+constexpr int OPER_BYTES = BM * BK * 2;             // 32 KB per operand slab
+constexpr int LDS_B_BASE = NSTAGE_A * OPER_BYTES;
+constexpr int GEMM_LDS_BYTES = (NSTAGE_A + NSTAGE_B) * OPER_BYTES;  // 160 KB
 constexpr int PANEL_M = 8;                          // tile-order panel width (L2 locality)
 
 enum EpiKind : int {
@@ -68,29 +70,29 @@ struct GemmArgs {
 // The LDS of gfx950 serves 256 B per clock (64 banks of 4 B): a 16-byte read is
 // processed 16 lanes at a time, an 8-byte read 32 lanes at a time, and is free of
 // bank conflicts when those lanes cover 256 distinct bytes modulo 256.
-// KC tile: 256 rows x 32 k, 64 B per row, 16-byte chunk c stored at c ^ ((row/4) & 3):
+// KC tile: 256 rows x 64 k, 128 B per row, 16-byte chunk c stored at c ^ ((row/2) & 7):
 // sixteen consecutive rows reading the same logical chunk touch every bank once.
 __device__ __forceinline__ uint32_t kc_off(int row, int chunk) {
-    return (uint32_t)(row * 64 + (((chunk) ^ ((row >> 2) & 3)) << 4));
+    return (uint32_t)(row * 128 + (((chunk) ^ ((row >> 1) & 7)) << 4));
 }
-// MNC tile: 32 k-rows x 256 columns, 512 B per k-row, 32-byte chunk c stored at
+// MNC tile: 64 k-rows x 256 columns, 512 B per k-row, 32-byte chunk c stored at
 // c ^ (2 * (krow & 3)): the 4 k-rows x 64 B that 32 lanes of a transposing read
 // touch land in 8 distinct 32-byte slots of the 256-byte bank window.
 __device__ __forceinline__ uint32_t mnc_off(int krow, int c32, int within) {
     return (uint32_t)(krow * 512 + (((c32) ^ ((krow & 3) << 1)) << 5) + within);
 }
 
-// s = 0, 1: the two k-steps of 16 inside a slab
-__device__ __forceinline__ bf16x8 lds_frag_kc(const char* tile, int row_base, int s, int lane) {
+// ks = 0..3: the four k-steps of 16 inside a slab
+__device__ __forceinline__ bf16x8 lds_frag_kc(const char* tile, int row_base, int ks, int lane) {
     int row = row_base + (lane & 31);
-    int chunk = 2 * s + (lane >> 5);
+    int chunk = 2 * ks + (lane >> 5);
     u32x4 v = *reinterpret_cast<const u32x4*>(tile + kc_off(row, chunk));
     return __builtin_bit_cast(bf16x8, v);
 }
 
-__device__ __forceinline__ bf16x8 lds_frag_mnc(const char* tile, int col_base, int s, int lane) {
+__device__ __forceinline__ bf16x8 lds_frag_mnc(const char* tile, int col_base, int ks, int lane) {
     int b = lane >> 4, i = lane & 15;
-    int krow = 16 * s + 8 * (b >> 1) + (i >> 2);
+    int krow = 16 * ks + 8 * (b >> 1) + (i >> 2);
     int c32 = (col_base >> 4) + (b & 1);
     int within = 8 * (i & 3);
     typedef __attribute__((address_space(3))) short4v* lds_ptr;
@@ -164,19 +166,19 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
 
     // ---- global -> LDS staging (direct-to-LDS buffer loads) ----------------------
     // A wave-wide 16-byte load deposits lane l at LDS base + 16*l, so each load
-    // fills one contiguous 1 KB region q of the operand slab (16 regions; wave w
-    // owns regions 2w, 2w+1).  The swizzle is applied on the global side: a lane
+    // fills one contiguous 1 KB region q of the operand slab (32 regions; wave w
+    // owns regions 4w..4w+3).  The swizzle is applied on the global side: a lane
     // fetches the chunk whose swizzled home is its own 16-byte slot.
-    //   KC : region q = rows 16q..16q+15;  lane -> row 16q + l/4, chunk (l%4) ^ ((l/16)%4)
-    //   MNC: region q = k-rows 2q, 2q+1;   lane -> krow 2q + l/32, slot p = l%32:
+    //   KC : region q = rows 8q..8q+7;   lane -> row 8q + l/8, chunk (l%8) ^ ((row/2)%8)
+    //   MNC: region q = k-rows 2q, 2q+1; lane -> krow 2q + l/32, slot p = l%32:
     //        32-byte chunk (p/2) ^ (2 * (krow & 3)), half p & 1
-    uint32_t a_goff[2], b_goff[2];     // byte offset of the lane's chunk at slab 0 (or OOB)
-    int a_kk[2], b_kk[2];              // k index (inside the slab) the validity test uses
+    uint32_t a_goff[4], b_goff[4];     // byte offset of the lane's chunk at slab 0 (or OOB)
+    int a_kk[4], b_kk[4];              // k index (inside the slab) the validity test uses
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int q = wave * 2 + i;
+    for (int i = 0; i < 4; ++i) {
+        const int q = wave * 4 + i;
         if (A_KC) {
-            int row = 16 * q + (lane >> 2), c = (lane & 3) ^ ((lane >> 4) & 3);
+            int row = 8 * q + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
             int gr = m0 + row;
             a_goff[i] = gr < Meff ? (uint32_t)(((int64_t)gr * P.lda + c * 8) * 2) : kOobOffset;
             a_kk[i] = c * 8;
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
             a_kk[i] = krow;
         }
         if (B_KC) {
-            int row = 16 * q + (lane >> 2), c = (lane & 3) ^ ((lane >> 4) & 3);
+            int row = 8 * q + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
             // SWIGLU: tile rows 0..127 are W_gate rows, 128..255 the same rows of W_up
             int gr = (EPI == EPI_SWIGLU) ? n0 + (row & 127) : n0 + row;
             b_goff[i] = gr < P.N ? (uint32_t)(((int64_t)gr * P.ldb + c * 8) * 2) : kOobOffset;
@@ -202,39 +204,38 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
         }
     }
     typedef __attribute__((address_space(3))) void* lds_void_ptr;
-    // issue the 4 loads of this wave for slab j (0-based inside this block's K range)
-    auto gload = [&](int j) {
+    // issue load i (0..3) of this wave's share of A slab j / B slab j (0-based inside this
+    // block's K range)
+    auto gload_a1 = [&](int j, int i) {
         const int kt = kt_begin + j;
         const int pair = kt >= ktiles_pair ? 1 : 0;
         const int kg = (kt - pair * ktiles_pair) * BK;  // k offset inside the pair
-        __amdgpu_buffer_rsrc_t ra_src = pair ? rA1 : rA0;
-        __amdgpu_buffer_rsrc_t rb_src = pair ? rB1 : rB0;
-        if (EPI == EPI_SWIGLU) rb_src = wave >= 4 ? rB1 : rB0;   // regions 8.. = rows 128..
-        char* sa = smem + (j % NSTAGE) * STAGE_BYTES + wave * 2048;
-        char* sb = sa + OPER_BYTES;
-        const uint32_t a_step = A_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.lda) * 2);
-        const uint32_t b_step = B_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.ldb) * 2);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            uint32_t off = (a_goff[i] != kOobOffset && (kg + a_kk[i]) < Keff) ? a_goff[i] + a_step
-                                                                              : kOobOffset;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(ra_src, (lds_void_ptr)(sa + i * 1024), 16,
-                                                     (int)off, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            uint32_t off = (b_goff[i] != kOobOffset && (kg + b_kk[i]) < Keff) ? b_goff[i] + b_step
-                                                                              : kOobOffset;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rb_src, (lds_void_ptr)(sb + i * 1024), 16,
-                                                     (int)off, 0, 0, 0);
-        }
+        __amdgpu_buffer_rsrc_t src = pair ? rA1 : rA0;
+        char* dst = smem + (j % NSTAGE_A) * OPER_BYTES + wave * 4096 + i * 1024;
+        const uint32_t step = A_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.lda) * 2);
+        uint32_t off = (a_goff[i] != kOobOffset && (kg + a_kk[i]) < Keff) ? a_goff[i] + step
+                                                                          : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
     };
-    // wait until at most `newer` slabs issued after the wanted one are still in flight
-    auto wait_slab = [&](int newer) {
-        if (newer >= 3) SKIPFFN_WAIT_VMCNT(12);
-        else if (newer == 2) SKIPFFN_WAIT_VMCNT(8);
-        else if (newer == 1) SKIPFFN_WAIT_VMCNT(4);
-        else SKIPFFN_WAIT_VMCNT(0);
+    auto gload_b1 = [&](int j, int i) {
+        const int kt = kt_begin + j;
+        const int pair = kt >= ktiles_pair ? 1 : 0;
+        const int kg = (kt - pair * ktiles_pair) * BK;
+        __amdgpu_buffer_rsrc_t src = pair ? rB1 : rB0;
+        if (EPI == EPI_SWIGLU) src = wave >= 4 ? rB1 : rB0;   // regions 16.. = rows 128..
+        char* dst = smem + LDS_B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096 + i * 1024;
+        const uint32_t step = B_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.ldb) * 2);
+        uint32_t off = (b_goff[i] != kOobOffset && (kg + b_kk[i]) < Keff) ? b_goff[i] + step
+                                                                          : kOobOffset;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+    };
+    auto gload_a = [&](int j) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) gload_a1(j, i);
+    };
+    auto gload_b = [&](int j) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) gload_b1(j, i);
     };
 
     f32x16 acc[4][2];
@@ -257,65 +258,90 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
 
     if (nk > 0) {
         // Ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4, i.e.
-        // the two row groups wm = 0, 1) run half a slab apart: while one issues its
-        // 16 MFMAs of slab j ("compute phase"), the other reads the fragments of its
-        // next slab from LDS, issues its share of the global loads and waits for
-        // them ("memory phase").  Phases are delimited by workgroup barriers; group 1
-        // takes one extra barrier before the loop and group 0 one after it, so the
-        // groups stay exactly one phase apart and every wave executes the same number
-        // of barriers.  The matrix pipe of each SIMD always has one wave in its
-        // compute phase.
+        // the two row groups wm = 0, 1) run one phase apart: while one issues the 16
+        // MFMAs of a half slab ("compute phase"), the other reads the fragments of
+        // its next half slab from LDS ("memory phase").  Phases are delimited by
+        // workgroup barriers; group 1 takes one extra barrier before the loop and
+        // group 0 one after it, so the groups stay exactly one phase apart and every
+        // wave executes the same number of barriers.  Per slab j a group runs
+        // M(j,0) C(j,0) M(j,1) C(j,1); with p = 4j:
+        //     phase      p        p+1      p+2      p+3
+        //     group 0    M(j,0)   C(j,0)   M(j,1)   C(j,1)
+        //     group 1    C(j-1,1) M(j,0)   C(j,0)   M(j,1)
+        // Global loads are issued in the memory phases, where a wave has nothing else
+        // to do while the address unit accepts them (about 16 clocks per wave-wide
+        // 16-byte load, during which the issuing wave is blocked): A(j+1) in M(j,0)
+        // and B(j+2) in M(j,1), four loads per wave and phase, so the address unit
+        // sees an even stream of 16 loads per phase.  Their target stages (those of
+        // A(j-1), B(j-1)) were last read in phase p-1.  Before the barrier that ends
+        // phase p+3 every wave waits until only its B(j+2) loads may still be in
+        // flight, so A(j+1) and B(j+1) are visible to all waves from phase p+4 on.
         bf16x8 af[2][4], bfr[2][2];
-        auto load_frags = [&](int j, int s) {
-            const char* sa = smem + (j % NSTAGE) * STAGE_BYTES;
-            const char* sb = sa + OPER_BYTES;
+        auto load_frags = [&](int j, int h) {
+            const char* sa = smem + (j % NSTAGE_A) * OPER_BYTES;
+            const char* sb = smem + LDS_B_BASE + (j % NSTAGE_B) * OPER_BYTES;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-                af[s][mt] = A_KC ? lds_frag_kc(sa, wm * 128 + mt * 32, s, lane)
-                                 : lds_frag_mnc(sa, wm * 128 + mt * 32, s, lane);
+            for (int s = 0; s < 2; ++s) {
 #pragma unroll
-            for (int nt = 0; nt < 2; ++nt)
-                bfr[s][nt] = B_KC ? lds_frag_kc(sb, b_rowbase[nt], s, lane)
-                                  : lds_frag_mnc(sb, b_rowbase[nt], s, lane);
-        };
-
-        // prologue: slabs 0 .. NSTAGE-2 in flight, slab 0 landed and visible
+                for (int mt = 0; mt < 4; ++mt)
+                    af[s][mt] = A_KC ? lds_frag_kc(sa, wm * 128 + mt * 32, 2 * h + s, lane)
+                                     : lds_frag_mnc(sa, wm * 128 + mt * 32, 2 * h + s, lane);
 #pragma unroll
-        for (int p = 0; p < NSTAGE - 1; ++p)
-            if (p < nk) gload(p);
-        wait_slab(nk - 1 < NSTAGE - 2 ? nk - 1 : NSTAGE - 2);
-        __builtin_amdgcn_s_barrier();
-        if (wm == 1) __builtin_amdgcn_s_barrier();       // group 1 starts one phase later
-
-        for (int j = 0; j < nk; ++j) {
-            // ---- memory phase of slab j.  Slab j is visible (prologue, or the waits of
-            // both groups in their memory phase j-1 followed by a barrier); the stage of
-            // slab j-1 has been read by both groups and can be refilled.
-            load_frags(j, 0);
-            load_frags(j, 1);
-            if (j + NSTAGE - 1 < nk) gload(j + NSTAGE - 1);
-            if (j + 1 < nk) {
-                const int newer = nk - (j + 2);           // slabs issued after j+1
-                wait_slab(newer < NSTAGE - 2 ? newer : NSTAGE - 2);
+                for (int nt = 0; nt < 2; ++nt)
+                    bfr[s][nt] = B_KC ? lds_frag_kc(sb, b_rowbase[nt], 2 * h + s, lane)
+                                      : lds_frag_mnc(sb, b_rowbase[nt], 2 * h + s, lane);
             }
-            SKIPFFN_WAIT_LGKMCNT0();                       // fragments are in registers
+        };
+        auto compute_phase = [&]() {
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            // ---- compute phase of slab j
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2)
+            for (int s = 0; s < 2; ++s)
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            af[s2][mt], bfr[s2][nt], acc[mt][nt], 0, 0, 0);
+                            af[s][mt], bfr[s][nt], acc[mt][nt], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto phase_barrier = [&]() {
             __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
+        };
+        // slab j+1 of both operands has landed; B(j+2), if it was issued, may still fly
+        auto wait_next_slab = [&](int j) {
+            if (j + 2 < nk) SKIPFFN_WAIT_VMCNT(4); else SKIPFFN_WAIT_VMCNT(0);
+        };
+
+        // prologue: A(0), B(0), B(1) issued; A(0) and B(0) landed and visible
+        gload_a(0);
+        gload_b(0);
+        if (nk > 1) { gload_b(1); SKIPFFN_WAIT_VMCNT(4); } else { SKIPFFN_WAIT_VMCNT(0); }
+        phase_barrier();
+        if (wm == 1) phase_barrier();                     // group 1 starts one phase later
+
+        for (int j = 0; j < nk; ++j) {
+            // M(j,0)
+            load_frags(j, 0);
+            if (j + 1 < nk) gload_a(j + 1);
+            SKIPFFN_WAIT_LGKMCNT0();
+            phase_barrier();
+            // C(j,0)
+            compute_phase();
+            phase_barrier();
+            // M(j,1)
+            load_frags(j, 1);
+            if (j + 2 < nk) gload_b(j + 2);
+            if (wm == 1) wait_next_slab(j);
+            SKIPFFN_WAIT_LGKMCNT0();
+            phase_barrier();
+            // C(j,1)
+            compute_phase();
+            if (wm == 0) wait_next_slab(j);
+            phase_barrier();
         }
-        if (wm == 0) __builtin_amdgcn_s_barrier();       // balances group 1's extra barrier
+        if (wm == 0) phase_barrier();                     // balances group 1's extra barrier
     }
 
     // ---- epilogue --------------------------------------------------------------
