@@ -38,6 +38,7 @@ constexpr int NSTAGE_A = 2, NSTAGE_B = 3;
 constexpr int OPER_BYTES = BM * BK * 2;             // 32 KB per operand slab
 constexpr int LDS_B_BASE = NSTAGE_A * OPER_BYTES;
 constexpr int GEMM_LDS_BYTES = (NSTAGE_A + NSTAGE_B) * OPER_BYTES;  // 160 KB
+constexpr int EPI_ROWS = 32;                         // rows of C staged per epilogue pass and row group
 constexpr int PANEL_M = 8;                          // tile-order panel width (L2 locality)
 
 enum EpiKind : int {
@@ -300,8 +301,10 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
                 for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
+                        // B fragment first: the accumulator then holds, per lane, one row m of
+                        // C and four consecutive columns n per register quad (see the epilogue)
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            af[s][mt], bfr[s][nt], acc[mt][nt], 0, 0, 0);
+                            bfr[s][nt], af[s][mt], acc[mt][nt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         };
         auto phase_barrier = [&]() {
@@ -345,75 +348,149 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
     }
 
     // ---- epilogue --------------------------------------------------------------
-    // acc[mt][nt][r] is C[row][col] with
-    //   row = m0 + wm*128 + mt*32 + 8*(r/4) + 4*(lane/32) + r%4
-    //   col = (tile column base) + lane%32
-    const int lrow = m0 + wm * 128 + 4 * (lane >> 5);
-    const int lcol = lane & 31;
+    // With the B fragment as first MFMA operand, acc[mt][nt][r] is C[row][col] with
+    //   row = m0 + wm*128 + mt*32 + lane%32
+    //   col = (tile column base) + nt*32 + 8*(r/4) + 4*(lane/32) + r%4
+    // i.e. each register quad r = 4g..4g+3 is four consecutive columns of one row.
+    // The tile leaves through LDS (free after the main loop): per pass mt, every
+    // row group (wm) dumps its 32 x 256 fp32 slice as 16-byte vectors, and after a
+    // barrier each thread takes row-contiguous chunks of 8 columns, applies the
+    // epilogue arithmetic and moves 16 bytes per global access.  Two staging
+    // buffers alternate, so one barrier per pass suffices.
+    constexpr int SLICE_COLS = (EPI == EPI_SWIGLU) ? 128 : 256;       // per staged matrix
+    constexpr int SLICE_STRIDE = SLICE_COLS * 4 + 16;                   // bytes; +16 spreads rows over banks
+    constexpr int SLICE_MATS = (EPI == EPI_SWIGLU) ? 2 : 1;             // G and U
+    constexpr int SLICE_BYTES = SLICE_MATS * EPI_ROWS * SLICE_STRIDE;   // per row group
+    static_assert(4 * SLICE_BYTES <= GEMM_LDS_BYTES, "staging must fit in LDS");
+    const int h = lane >> 5;
+    const int tg = t & 255;                       // thread index inside the row group
+    constexpr int CHUNKS_PER_ROW = SLICE_COLS / 8;
+    constexpr int CHUNKS_PER_THREAD = EPI_ROWS * CHUNKS_PER_ROW / 256;
 
-    if (EPI == EPI_SWIGLU) {
-        bf16_t* H = static_cast<bf16_t*>(P.out0);
-        bf16_t* G = static_cast<bf16_t*>(P.out1);
-        bf16_t* U = static_cast<bf16_t*>(P.out2);
-        const int col = n0 + wn * 32 + lcol;
-        if (col < P.N) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < 4; ++mt) {
+        char* sbuf = smem + ((mt & 1) * 2 + wm) * SLICE_BYTES;
+        // ---- dump this wave's part of the slice
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int row = lrow + mt * 32 + 8 * (r >> 2) + (r & 3);
-                    if (row < Meff) {
-                        float g = acc[mt][0][r], u = acc[mt][1][r];
-                        uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
-                        H[o] = f32_to_bf16(g * sigmoid_f(g) * u);
-                        if (G != nullptr) {
-                            G[o] = f32_to_bf16(g);
-                            U[o] = f32_to_bf16(u);
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v = {acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2],
+                           acc[mt][nt][4 * g + 3]};
+                int col, mat;
+                if (EPI == EPI_SWIGLU) { mat = nt; col = wn * 32 + 8 * g + 4 * h; }
+                else                   { mat = 0;  col = wn * 64 + nt * 32 + 8 * g + 4 * h; }
+                *reinterpret_cast<f32x4*>(sbuf + mat * EPI_ROWS * SLICE_STRIDE +
+                                          (lane & 31) * SLICE_STRIDE + col * 4) = v;
+            }
+        __syncthreads();
+        // ---- row-contiguous chunks of 8 columns
+#pragma unroll
+        for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
+            const int cid = tg + 256 * i;
+            const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
+            const int row = m0 + wm * 128 + mt * 32 + r;
+            const int col = n0 + c * 8;
+            if (row >= Meff || col >= P.N) continue;
+            // lanes c >= 8 (mod 16) read their second half first: conflict-free 16-byte reads
+            const int swap = (c >> 3) & 1;
+            float v[8], w[8];
+            {
+                const char* src = sbuf + r * SLICE_STRIDE + c * 32;
+                f32x4 a = *reinterpret_cast<const f32x4*>(src + (swap ? 16 : 0));
+                f32x4 b = *reinterpret_cast<const f32x4*>(src + (swap ? 0 : 16));
+                f32x4 lo = swap ? b : a, hi = swap ? a : b;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { v[k] = lo[k]; v[4 + k] = hi[k]; }
+            }
+            if (EPI == EPI_SWIGLU) {
+                const char* src = sbuf + EPI_ROWS * SLICE_STRIDE + r * SLICE_STRIDE + c * 32;
+                f32x4 a = *reinterpret_cast<const f32x4*>(src + (swap ? 16 : 0));
+                f32x4 b = *reinterpret_cast<const f32x4*>(src + (swap ? 0 : 16));
+                f32x4 lo = swap ? b : a, hi = swap ? a : b;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { w[k] = lo[k]; w[4 + k] = hi[k]; }
+                const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
+                u32x4 ph, pg, pu;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float g0 = v[2 * k], g1 = v[2 * k + 1], u0 = w[2 * k], u1 = w[2 * k + 1];
+                    ph[k] = pack_bf16x2(g0 * sigmoid_f(g0) * u0, g1 * sigmoid_f(g1) * u1);
+                    pg[k] = pack_bf16x2(g0, g1);
+                    pu[k] = pack_bf16x2(u0, u1);
+                }
+                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o) = ph;
+                if (P.out1 != nullptr) {
+                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out1) + o) = pg;
+                    *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out2) + o) = pu;
+                }
+            } else if (EPI == EPI_STORE) {
+                const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
+                if (P.out_f32) {
+                    f32x4* O = reinterpret_cast<f32x4*>(static_cast<float*>(P.out0) + o);
+                    f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+                    if (P.accumulate) { lo += O[0]; hi += O[1]; }
+                    O[0] = lo;
+                    O[1] = hi;
+                } else {
+                    u32x4* O = reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o);
+                    if (P.accumulate) {
+                        u32x4 old = *O;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            v[2 * k] += bf16lo_to_f32(old[k]);
+                            v[2 * k + 1] += bf16hi_to_f32(old[k]);
                         }
                     }
+                    u32x4 pk;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) pk[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+                    *O = pk;
                 }
-        }
-        return;
-    }
-
+            } else if (EPI == EPI_PARTIAL) {
+                f32x4* O = reinterpret_cast<f32x4*>(P.partial + ((int64_t)z * P.M + row) * P.N + col);
+                f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+                O[0] = lo;
+                O[1] = hi;
+            } else if (EPI == EPI_RESID_SCATTER) {
+                const uint32_t o = (uint32_t)P.idx[row] * (uint32_t)P.ldo + (uint32_t)col;
+                if (!P.no_residual) {
+                    u32x4 x = *reinterpret_cast<const u32x4*>(P.e0 + o);
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            const int col = n0 + wn * 64 + nt * 32 + lcol;
-            if (col >= P.N) continue;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int row = lrow + mt * 32 + 8 * (r >> 2) + (r & 3);
-                if (row >= Meff) continue;
-                float v = acc[mt][nt][r];
-                if (EPI == EPI_STORE) {
-                    uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
-                    if (P.out_f32) {
-                        float* O = static_cast<float*>(P.out0);
-                        O[o] = P.accumulate ? O[o] + v : v;
-                    } else {
-                        bf16_t* O = static_cast<bf16_t*>(P.out0);
-                        O[o] = f32_to_bf16(P.accumulate ? bf16_to_f32(O[o]) + v : v);
+                    for (int k = 0; k < 4; ++k) {
+                        v[2 * k] += bf16lo_to_f32(x[k]);
+                        v[2 * k + 1] += bf16hi_to_f32(x[k]);
                     }
-                } else if (EPI == EPI_PARTIAL) {
-                    P.partial[((int64_t)z * P.M + row) * P.N + col] = v;
-                } else if (EPI == EPI_RESID_SCATTER) {
-                    uint32_t o = (uint32_t)P.idx[row] * (uint32_t)P.ldo + (uint32_t)col;
-                    bf16_t* O = static_cast<bf16_t*>(P.out0);
-                    float res = P.no_residual ? 0.0f : bf16_to_f32(P.e0[o]);
-                    O[o] = f32_to_bf16(res + v);
-                } else if (EPI == EPI_SWIGLU_BWD) {
-                    uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
-                    float g = bf16_to_f32(P.e0[o]), u = bf16_to_f32(P.e1[o]);
-                    float sg = sigmoid_f(g);
-                    float dg = v * u * sg * (1.0f + g * (1.0f - sg));
-                    float du = v * g * sg;
-                    static_cast<bf16_t*>(P.out0)[o] = f32_to_bf16(dg);
-                    static_cast<bf16_t*>(P.out1)[o] = f32_to_bf16(du);
                 }
+                u32x4 pk;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) pk[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o) = pk;
+            } else if (EPI == EPI_SWIGLU_BWD) {
+                const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
+                u32x4 gq = *reinterpret_cast<const u32x4*>(P.e0 + o);
+                u32x4 uq = *reinterpret_cast<const u32x4*>(P.e1 + o);
+                u32x4 dgq, duq;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float gg[2] = {bf16lo_to_f32(gq[k]), bf16hi_to_f32(gq[k])};
+                    float uu[2] = {bf16lo_to_f32(uq[k]), bf16hi_to_f32(uq[k])};
+                    float dg[2], du[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        float sg = sigmoid_f(gg[e]);
+                        float dh = v[2 * k + e];
+                        dg[e] = dh * uu[e] * sg * (1.0f + gg[e] * (1.0f - sg));
+                        du[e] = dh * gg[e] * sg;
+                    }
+                    dgq[k] = pack_bf16x2(dg[0], dg[1]);
+                    duq[k] = pack_bf16x2(du[0], du[1]);
+                }
+                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o) = dgq;
+                *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out1) + o) = duq;
             }
         }
+    }
 }
 
 }  // namespace skipffn
