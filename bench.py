@@ -48,7 +48,7 @@ def kernel_work(name, R, T, C, I, dw_bytes):
         "gemm_down": ("mfma", 2 * R * C * I),
         "gemm_dh_swiglu_bwd": ("mfma", 2 * R * C * I),
         "gemm_dw_down": ("mfma", 2 * R * C * I),
-        "gemm_dw_gate_up": ("mfma", 2 * R * C * I),
+        "gemm_dw_gate_up": ("mfma", 4 * R * C * I),      # dW_gate and dW_up in one launch
         "gemm_dxn": ("mfma", 4 * R * C * I),
         "compact": ("hbm", T + 4 * R),
         "gather_rmsnorm": ("hbm", 2 * rc * 2 + 4 * R),

@@ -424,14 +424,14 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         profile_mark_end(KC_GEMM_DW_DOWN, s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn
-    for (int which = 0; which < 2; ++which) {
+    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn : one launch, two problems
+    {
         GemmArgs a{};
         a.M = (int)I; a.N = (int)C; a.K = (int)Rb; a.k_dev = r_dev;
-        a.A0 = which == 0 ? dG : dU; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
+        a.A0 = dG; a.A1 = dU; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
         a.B0 = xn; a.ldb = (int)C; a.b_bytes = (uint32_t)(Rb * C * 2);
-        a.pairs = 1; a.splits = 1;
-        a.out0 = which == 0 ? dw_gate : dw_up; a.ldo = (int)C; a.out_f32 = f32; a.accumulate = accum;
+        a.pairs = 1; a.splits = 1; a.batch = 2;
+        a.out0 = dw_gate; a.out1 = dw_up; a.ldo = (int)C; a.out_f32 = f32; a.accumulate = accum;
         profile_mark_begin(KC_GEMM_DW_GATE_UP, s);
         e = launch_gemm(false, false, EPI_STORE, a, s);
         profile_mark_end(KC_GEMM_DW_GATE_UP, s);

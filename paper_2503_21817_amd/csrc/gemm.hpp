@@ -57,6 +57,7 @@ struct GemmArgs {
     const bf16_t* B0; const bf16_t* B1; int ldb; uint32_t b_bytes;
     int pairs;                   // 1, or 2: K runs over (A0,B0) then (A1,B1)
     int splits;                  // split-K factor
+    int batch;                   // 1, or 2 independent problems sharing B: (A0 -> out0), (A1 -> out1); pairs == 1
     int tiles_m, tiles_n;
     void* out0; void* out1; void* out2; int ldo;
     const bf16_t* e0; const bf16_t* e1; int lde;
@@ -145,6 +146,14 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
 
     int tm, tn, z;
     tile_of_block(blockIdx.x, gridDim.x, P.tiles_m, P.tiles_n, tm, tn, z);
+    // batched launch (two problems in one grid, used for dW_gate / dW_up): the upper half of
+    // the z range is problem 1
+    const bool second = P.batch == 2 && z >= P.splits;
+    if (second) {
+        z -= P.splits;
+        P.A0 = P.A1;
+        P.out0 = P.out1;
+    }
 
     const int Meff = effective_rows(P.M, P.m_dev);
     const int Keff = effective_rows(P.K, P.k_dev);

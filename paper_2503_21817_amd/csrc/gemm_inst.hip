@@ -22,7 +22,7 @@ hipError_t gemm_init() {
 
 template <bool A_KC, bool B_KC, int EPI>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
-    const unsigned blocks = (unsigned)(a.tiles_m * a.tiles_n * a.splits);
+    const unsigned blocks = (unsigned)(a.tiles_m * a.tiles_n * a.splits * a.batch);
     hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI>), dim3(blocks), dim3(GEMM_THREADS),
                        GEMM_LDS_BYTES, s, a);
     return hipGetLastError();
@@ -32,6 +32,7 @@ hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (epi == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     if (a.splits < 1) a.splits = 1;
+    if (a.batch < 1) a.batch = 1;
     if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
     if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU>(a, s);
     if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL>(a, s);
