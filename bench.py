@@ -46,9 +46,8 @@ def kernel_work(name, R, T, C, I, dw_bytes):
     table = {
         "gemm_gate_up_swiglu": ("mfma", 4 * R * C * I),
         "gemm_down": ("mfma", 2 * R * C * I),
-        "gemm_dh_swiglu_bwd": ("mfma", 2 * R * C * I),
-        "gemm_dw_down": ("mfma", 2 * R * C * I),
-        "gemm_dw_gate_up": ("mfma", 4 * R * C * I),      # dW_gate and dW_up in one launch
+        "gemm_dh_swiglu_bwd+dw_down": ("mfma", 4 * R * C * I),    # two GEMMs in one grid
+        "gemm_dw_gate_up": ("mfma", 4 * R * C * I),               # dW_gate and dW_up in one grid
         "gemm_dxn": ("mfma", 4 * R * C * I),
         "compact": ("hbm", T + 4 * R),
         "gather_rmsnorm": ("hbm", 2 * rc * 2 + 4 * R),

@@ -118,8 +118,8 @@ namespace skipffn {
 const char* kernel_class_name(int kc) {
     static const char* names[KC_COUNT] = {
         "compact", "gather_rmsnorm", "gemm_gate_up_swiglu", "gemm_down", "resid_scatter",
-        "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd", "gemm_dw_down",
-        "gemm_dw_gate_up", "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero"};
+        "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd+dw_down", "gemm_dw_gate_up",
+        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero"};
     return (kc >= 0 && kc < KC_COUNT) ? names[kc] : "?";
 }
 
@@ -398,7 +398,8 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     e = launch_gather_rows(grad_out, dY, C * 2, idx, (int)Rb, r_dev, s);
     if (e != hipSuccess) return hip_fail(e);
 
-    // dH = dY * W_down, fused with the SiLU*mul backward: dG, dU
+    // dH = dY * W_down fused with the SiLU*mul backward (-> dG, dU), and, in the same grid
+    // (it depends only on dY and H), dW_down [C, I] = dY^T * H
     {
         GemmArgs a{};
         a.M = (int)Rb; a.N = (int)I; a.K = (int)C; a.m_dev = r_dev;
@@ -406,22 +407,15 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         a.B0 = static_cast<const bf16_t*>(w_down); a.ldb = (int)I; a.b_bytes = (uint32_t)(C * I * 2);
         a.pairs = 1; a.splits = 1;
         a.out0 = dG; a.out1 = dU; a.ldo = (int)I; a.e0 = G; a.e1 = U; a.lde = (int)I;
-        profile_mark_begin(KC_GEMM_DH, s);
-        e = launch_gemm(true, false, EPI_SWIGLU_BWD, a, s);
-        profile_mark_end(KC_GEMM_DH, s);
-        if (e != hipSuccess) return hip_fail(e);
-    }
-    // dW_down [C, I] = dY^T * H
-    {
-        GemmArgs a{};
-        a.M = (int)C; a.N = (int)I; a.K = (int)Rb; a.k_dev = r_dev;
-        a.A0 = dY; a.lda = (int)C; a.a_bytes = (uint32_t)(Rb * C * 2);
-        a.B0 = H; a.ldb = (int)I; a.b_bytes = (uint32_t)(Rb * I * 2);
-        a.pairs = 1; a.splits = 1;
-        a.out0 = dw_down; a.ldo = (int)I; a.out_f32 = f32; a.accumulate = accum;
-        profile_mark_begin(KC_GEMM_DW_DOWN, s);
-        e = launch_gemm(false, false, EPI_STORE, a, s);
-        profile_mark_end(KC_GEMM_DW_DOWN, s);
+        GemmArgs b{};
+        b.M = (int)C; b.N = (int)I; b.K = (int)Rb; b.k_dev = r_dev;
+        b.A0 = dY; b.lda = (int)C; b.a_bytes = (uint32_t)(Rb * C * 2);
+        b.B0 = H; b.ldb = (int)I; b.b_bytes = (uint32_t)(Rb * I * 2);
+        b.pairs = 1; b.splits = 1;
+        b.out0 = dw_down; b.ldo = (int)I; b.out_f32 = f32; b.accumulate = accum;
+        profile_mark_begin(KC_GEMM_DH_DWDOWN, s);
+        e = launch_gemm_dual(DUAL_DH_DWDOWN, a, b, s);
+        profile_mark_end(KC_GEMM_DH_DWDOWN, s);
         if (e != hipSuccess) return hip_fail(e);
     }
     // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn : one launch, two problems
@@ -437,7 +431,8 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         profile_mark_end(KC_GEMM_DW_GATE_UP, s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    // dxn = dG * W_gate + dU * W_up  (K runs over both pairs), fp32 split-K slabs
+    // dxn = dG * W_gate + dU * W_up  (K runs over both pairs), fp32 split-K slabs.  (Sharing a
+    // grid with the dW GEMMs above was measured slower: both are already well balanced.)
     int splits;
     {
         GemmArgs a{};

@@ -135,8 +135,9 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
     tm = p * PANEL_M + (in_panel - tn * pm);
 }
 
+// One workgroup's share of a GEMM: `block` of `nblocks` in the launch order of this problem.
 template <bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
+__device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const int nblocks) {
     extern __shared__ __align__(16) char smem[];
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -145,7 +146,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
     const int wn = wave & 3;       // 0..3
 
     int tm, tn, z;
-    tile_of_block(blockIdx.x, gridDim.x, P.tiles_m, P.tiles_n, tm, tn, z);
+    tile_of_block(block, nblocks, P.tiles_m, P.tiles_n, tm, tn, z);
     // batched launch (two problems in one grid, used for dW_gate / dW_up): the upper half of
     // the z range is problem 1
     const bool second = P.batch == 2 && z >= P.splits;
@@ -499,6 +500,27 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
                 *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out1) + o) = duq;
             }
         }
+    }
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
+    gemm_block<A_KC, B_KC, EPI>(P, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Two independent GEMMs in one grid: workgroups [0, nblocks0) run problem 0 (launched
+// first: give it the longer tiles), the rest problem 1, so the last round of one fills
+// with tiles of the other instead of leaving CUs idle.  nblocks0 is a multiple of 8 (the
+// host pads with workgroups that exit at once) so that both problems see the round-robin
+// XCD assignment from its start.
+template <bool A0_KC, bool B0_KC, int EPI0, bool A1_KC, bool B1_KC, int EPI1>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_dual_kernel(GemmArgs P0, GemmArgs P1,
+                                                                      int nblocks0, int real0) {
+    const int b = (int)blockIdx.x;
+    if (b < nblocks0) {
+        if (b < real0) gemm_block<A0_KC, B0_KC, EPI0>(P0, b, real0);
+    } else {
+        gemm_block<A1_KC, B1_KC, EPI1>(P1, b - nblocks0, (int)gridDim.x - nblocks0);
     }
 }
 

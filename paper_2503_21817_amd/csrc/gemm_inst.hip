@@ -17,6 +17,9 @@ hipError_t gemm_init() {
     if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
     if ((e = set_lds_limit<false, false, EPI_STORE>()) != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, false, false, EPI_STORE>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e != hipSuccess) return e;
     return hipSuccess;
 }
 
@@ -28,11 +31,28 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s) {
+static void finish_args(int epi, GemmArgs& a) {
     a.tiles_m = (a.M + BM - 1) / BM;
     a.tiles_n = (epi == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     if (a.splits < 1) a.splits = 1;
     if (a.batch < 1) a.batch = 1;
+}
+
+hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s) {
+    if (which != DUAL_DH_DWDOWN) return hipErrorInvalidValue;
+    finish_args(EPI_SWIGLU_BWD, a0);
+    finish_args(EPI_STORE, a1);
+    const int real0 = a0.tiles_m * a0.tiles_n * a0.splits * a0.batch;
+    const int n0 = (real0 + 7) / 8 * 8;
+    const int n1 = a1.tiles_m * a1.tiles_n * a1.splits * a1.batch;
+    if (real0 <= 0 || n1 <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, false, false, EPI_STORE>),
+                       dim3((unsigned)(n0 + n1)), dim3(GEMM_THREADS), GEMM_LDS_BYTES, s, a0, a1, n0, real0);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s) {
+    finish_args(epi, a);
     if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
     if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU>(a, s);
     if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL>(a, s);

@@ -19,9 +19,8 @@ enum KernelClass : int {
     KC_RESID_SCATTER,
     KC_PASSTHROUGH,
     KC_GATHER_ROWS,
-    KC_GEMM_DH,
-    KC_GEMM_DW_DOWN,
-    KC_GEMM_DW_GATE_UP,
+    KC_GEMM_DH_DWDOWN,      // dH + SwiGLU backward and dW_down in one grid
+    KC_GEMM_DW_GATE_UP,     // dW_gate and dW_up, batched in one grid
     KC_GEMM_DXN,
     KC_RMSNORM_BWD,
     KC_FILL,
@@ -62,5 +61,10 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation (once per process)
 // layouts: a_kc / b_kc as in gemm.hpp
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& args, hipStream_t s);
+// two independent GEMMs in one grid (problem 0 is dispatched first)
+enum DualKind : int {
+    DUAL_DH_DWDOWN = 0    // <KC,MNC,SWIGLU_BWD> (dH -> dG, dU)  +  <MNC,MNC,STORE> (dW_down)
+};
+hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s);
 
 }  // namespace skipffn
