@@ -218,6 +218,7 @@ hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row
 //   dx = rstd * (dxh - xh * mean_c(dxh * xh));  dX[idx[r]] = bf16(dY[r] + dx)
 // dxn arrives as `splits` fp32 partial sums [z][r][c] (the split-K slabs of the
 // dG*W_gate + dU*W_up GEMM), added here in z order.
+template <bool IN_REGS>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     const float* __restrict__ part, int splits, int Rbound, const int32_t* __restrict__ r_dev,
     int C, const bf16_t* __restrict__ xrows, const float* __restrict__ rstd_in,
@@ -253,27 +254,53 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
             for (int j = 0; j < 8; ++j) d[j] *= g[j];
         }
     };
-
-    float dot = 0.0f;
-    for (int c = lane; c < chunks; c += 64) {
-        float d[8], x[8];
-        load_dxh(c, d);
-        unpack8(xs[c], x);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) dot += d[j] * (x[j] * rstd);
-    }
-    dot = wave_sum(dot) / (float)C;
-
     const u32x4* dys = reinterpret_cast<const u32x4*>(dY + (int64_t)r * C);
     u32x4* out = reinterpret_cast<u32x4*>(dX + (int64_t)idx[r] * C);
-    for (int c = lane; c < chunks; c += 64) {
-        float d[8], x[8], gy[8], o[8];
-        load_dxh(c, d);
-        unpack8(xs[c], x);
+    auto emit = [&](int c, const float* d, const float* x, float dot) {
+        float gy[8], o[8];
         unpack8(dys[c], gy);
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[j] = gy[j] + rstd * (d[j] - (x[j] * rstd) * dot);
         out[c] = pack8(o);
+    };
+
+    if (IN_REGS) {
+        // the row (sum of the split-K slabs, and x) is read once and kept in registers
+        constexpr int MAXV = 8;          // C <= 64 * 8 * 8 = 4096
+        float d[MAXV][8], x[MAXV][8];
+        float dot = 0.0f;
+#pragma unroll
+        for (int v = 0; v < MAXV; ++v) {
+            int c = lane + 64 * v;
+            if (c < chunks) {
+                load_dxh(c, d[v]);
+                unpack8(xs[c], x[v]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) dot += d[v][j] * (x[v][j] * rstd);
+            }
+        }
+        dot = wave_sum(dot) / (float)C;
+#pragma unroll
+        for (int v = 0; v < MAXV; ++v) {
+            int c = lane + 64 * v;
+            if (c < chunks) emit(c, d[v], x[v], dot);
+        }
+    } else {
+        float dot = 0.0f;
+        for (int c = lane; c < chunks; c += 64) {
+            float d[8], x[8];
+            load_dxh(c, d);
+            unpack8(xs[c], x);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dot += d[j] * (x[j] * rstd);
+        }
+        dot = wave_sum(dot) / (float)C;
+        for (int c = lane; c < chunks; c += 64) {
+            float d[8], x[8];
+            load_dxh(c, d);
+            unpack8(xs[c], x);
+            emit(c, d, x, dot);
+        }
     }
 }
 
@@ -284,8 +311,12 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int 
     if (R <= 0) return hipSuccess;
     dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
     profile_mark_begin(KC_RMSNORM_BWD, s);
-    hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel, grid, block, 0, s, dxn_partial, splits, R, r_dev,
-                       C, xrows, rstd, gain, dY, idx, dX);
+    if (C <= 4096)
+        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<true>, grid, block, 0, s, dxn_partial, splits,
+                           R, r_dev, C, xrows, rstd, gain, dY, idx, dX);
+    else
+        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<false>, grid, block, 0, s, dxn_partial, splits,
+                           R, r_dev, C, xrows, rstd, gain, dY, idx, dX);
     profile_mark_end(KC_RMSNORM_BWD, s);
     return hipGetLastError();
 }
