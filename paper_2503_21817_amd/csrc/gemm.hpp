@@ -92,16 +92,31 @@ __device__ __forceinline__ bf16x8 lds_frag_kc(const char* tile, int row_base, in
     return __builtin_bit_cast(bf16x8, v);
 }
 
+// The transposing read is issued through inline assembly: for the builtin form the
+// compiler cannot tell that the read does not alias the direct-to-LDS loads in flight and
+// puts s_waitcnt vmcnt(0) in front of it, which would serialise the whole load pipeline.
+// The assembly form is invisible to that analysis, so the CALLER must wait for lgkmcnt(0)
+// before the returned registers are consumed (the main loop does, at the end of every
+// memory phase).
+__device__ __forceinline__ u32x2 ds_read_tr16_b64(uint32_t lds_addr) {
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(lds_addr));
+    return v;
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
+    typedef __attribute__((address_space(3))) const char* lds_cptr;
+    return (uint32_t)(uintptr_t)(lds_cptr)p;
+}
+
 __device__ __forceinline__ bf16x8 lds_frag_mnc(const char* tile, int col_base, int ks, int lane) {
     int b = lane >> 4, i = lane & 15;
     int krow = 16 * ks + 8 * (b >> 1) + (i >> 2);
     int c32 = (col_base >> 4) + (b & 1);
     int within = 8 * (i & 3);
-    typedef __attribute__((address_space(3))) short4v* lds_ptr;
-    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + mnc_off(krow, c32, within)));
-    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(tile + mnc_off(krow + 4, c32, within)));
-    typedef __attribute__((ext_vector_type(8))) short short8v;
-    short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    const uint32_t base = lds_addr_of(tile);
+    u32x2 lo = ds_read_tr16_b64(base + mnc_off(krow, c32, within));
+    u32x2 hi = ds_read_tr16_b64(base + mnc_off(krow + 4, c32, within));
+    u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
     return __builtin_bit_cast(bf16x8, both);
 }
 
