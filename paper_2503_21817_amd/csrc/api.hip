@@ -81,10 +81,13 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     return w;
 }
 
-struct BwdWs { size_t dy, dg, du, partial, total; };
+inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
+
+struct BwdWs { size_t dy, dyT, dg, du, partial, total; };
 BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
     BwdWs w; size_t o = 0;
     w.dy = o; o += align_up((size_t)R * C * 2);
+    w.dyT = o; o += align_up((size_t)C * ld_transposed(R) * 2);
     w.dg = o; o += align_up((size_t)R * I * 2);
     w.du = o; o += align_up((size_t)R * I * 2);
     w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
@@ -394,8 +397,11 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     bf16_t* dU = reinterpret_cast<bf16_t*>(ws + W.du);
     float* partial = reinterpret_cast<float*>(ws + W.partial);
 
-    // dY = dOut[idx]
-    e = launch_gather_rows(grad_out, dY, C * 2, idx, (int)Rb, r_dev, s);
+    // dY = dOut[idx], and its transposed copy dY^T [C][ldT] for the dW_down GEMM
+    bf16_t* dYT = reinterpret_cast<bf16_t*>(ws + W.dyT);
+    const int ldT = (int)ld_transposed(Rb);
+    e = launch_gather_transpose(static_cast<const bf16_t*>(grad_out), (int)C, idx, (int)Rb, r_dev, dY,
+                                dYT, ldT, s);
     if (e != hipSuccess) return hip_fail(e);
 
     // dH = dY * W_down fused with the SiLU*mul backward (-> dG, dU), and, in the same grid
@@ -409,7 +415,7 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         a.out0 = dG; a.out1 = dU; a.ldo = (int)I; a.e0 = G; a.e1 = U; a.lde = (int)I;
         GemmArgs b{};
         b.M = (int)C; b.N = (int)I; b.K = (int)Rb; b.k_dev = r_dev;
-        b.A0 = dY; b.lda = (int)C; b.a_bytes = (uint32_t)(Rb * C * 2);
+        b.A0 = dYT; b.lda = ldT; b.a_bytes = (uint32_t)(C * (int64_t)ldT * 2);   // K (= R) contiguous
         b.B0 = H; b.ldb = (int)I; b.b_bytes = (uint32_t)(Rb * I * 2);
         b.pairs = 1; b.splits = 1;
         b.out0 = dw_down; b.ldo = (int)I; b.out_f32 = f32; b.accumulate = accum;

@@ -47,6 +47,11 @@ hipError_t launch_resid_scatter(const float* partial, int splits, int R, const i
 // dst[r] = src[idx[r]]  (rows of row_bytes, multiple of 16)
 hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, const int32_t* idx,
                               int R, const int32_t* r_dev, hipStream_t s);
+// dst[r] = src[idx ? idx[r] : r] (dst optional) and the transposed copy dstT[c][r], leading
+// dimension ldT (multiple of 8, >= R bound), columns r >= R zero
+hipError_t launch_gather_transpose(const bf16_t* src, int C, const int32_t* idx, int R,
+                                   const int32_t* r_dev, bf16_t* dst, bf16_t* dstT, int ldT,
+                                   hipStream_t s);
 // copy every row t of src to dst that is NOT listed in idx (skipped tokens)
 hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row_bytes,
                               const int32_t* idx, int R, const int32_t* r_dev, hipStream_t s);
@@ -63,7 +68,7 @@ hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& args, hipStream_t s);
 // two independent GEMMs in one grid (problem 0 is dispatched first)
 enum DualKind : int {
-    DUAL_DH_DWDOWN = 0    // <KC,MNC,SWIGLU_BWD> (dH -> dG, dU)  +  <MNC,MNC,STORE> (dW_down)
+    DUAL_DH_DWDOWN = 0    // <KC,MNC,SWIGLU_BWD> (dH -> dG, dU)  +  <KC,MNC,STORE> (dW_down = dY^T * H)
 };
 hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s);
 

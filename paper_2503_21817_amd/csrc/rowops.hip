@@ -182,6 +182,66 @@ hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, con
     return hipGetLastError();
 }
 
+// ---- row gather with a transposed copy ------------------------------------------------------
+// dst[r][:] = src[row(r)][:] (optional) and dstT[c][r] = src[row(r)][c], where row(r) = idx[r]
+// (or r when idx is null).  dstT has leading dimension ldT (a multiple of 8 >= the row
+// bound); columns r >= R of dstT are written as zeros so that K-slabs reading past R see
+// zeros.  The weight-gradient GEMMs contract over R: a copy with R contiguous lets them read
+// this operand with plain 16-byte LDS reads instead of transposing ones.
+constexpr int TR_TILE = 64;
+__global__ __launch_bounds__(256) void gather_transpose_kernel(
+    const bf16_t* __restrict__ src, int C, const int32_t* __restrict__ idx, int Rbound,
+    const int32_t* __restrict__ r_dev, bf16_t* __restrict__ dst, bf16_t* __restrict__ dstT, int ldT) {
+    __shared__ bf16_t tile[TR_TILE][TR_TILE + 2];
+    const int R = effective_rows(Rbound, r_dev);
+    const int r0 = blockIdx.x * TR_TILE, c0 = blockIdx.y * TR_TILE;
+    const int t = threadIdx.x;
+    // phase 1: 64 rows x 64 columns, 16 bytes per access
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = t + 256 * i;
+        const int rr = q >> 3, ch = q & 7;
+        const int r = r0 + rr, c = c0 + ch * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r < R && c < C) {
+            const int64_t srow = idx ? (int64_t)idx[r] : (int64_t)r;
+            v = *reinterpret_cast<const u32x4*>(src + srow * C + c);
+            if (dst) *reinterpret_cast<u32x4*>(dst + (int64_t)r * C + c) = v;
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            tile[rr][ch * 8 + 2 * k] = (bf16_t)(v[k] & 0xffffu);
+            tile[rr][ch * 8 + 2 * k + 1] = (bf16_t)(v[k] >> 16);
+        }
+    }
+    __syncthreads();
+    // phase 2: 64 output rows (columns of src) x 64 r values = 8 chunks of 16 bytes each
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int q = t + 256 * i;
+        const int cc = q >> 3, ch = q & 7;
+        const int c = c0 + cc, r = r0 + ch * 8;
+        if (c < C && r < ldT) {
+            u32x4 v;
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                v[k] = (uint32_t)tile[ch * 8 + 2 * k][cc] | ((uint32_t)tile[ch * 8 + 2 * k + 1][cc] << 16);
+            *reinterpret_cast<u32x4*>(dstT + (int64_t)c * ldT + r) = v;
+        }
+    }
+}
+
+hipError_t launch_gather_transpose(const bf16_t* src, int C, const int32_t* idx, int R,
+                                   const int32_t* r_dev, bf16_t* dst, bf16_t* dstT, int ldT,
+                                   hipStream_t s) {
+    if (R <= 0 || C <= 0) return hipSuccess;
+    dim3 grid((ldT + TR_TILE - 1) / TR_TILE, (C + TR_TILE - 1) / TR_TILE), block(256);
+    profile_mark_begin(KC_GATHER_ROWS, s);
+    hipLaunchKernelGGL(gather_transpose_kernel, grid, block, 0, s, src, C, idx, R, r_dev, dst, dstT, ldT);
+    profile_mark_end(KC_GATHER_ROWS, s);
+    return hipGetLastError();
+}
+
 // ---- bit copy of skipped rows (out-of-place calls) ---------------------------------------
 // A row t is copied unless a binary search finds it in the ascending list idx.
 __global__ __launch_bounds__(ROW_THREADS) void passthrough_kernel(
