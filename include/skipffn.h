@@ -89,7 +89,7 @@ int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx,
  *   w_gate, w_up bf16 [I, C]; w_down bf16 [C, I]
  *   saved   NULL, or a buffer of skipffn_saved_bytes(R_max, C, I) bytes that
  *           receives what backward needs (gathered input rows, normalised
- *           rows, 1/rms, gate, up and hidden activations); required for
+ *           rows and their transpose, 1/rms, gate, up and hidden activations); required for
  *           training because an in-place forward overwrites its input.
  *   workspace: at least skipffn_forward_workspace_bytes(R_max, C, I, saved != NULL)
  * where R_max = R if R >= 0 else T.
@@ -141,7 +141,9 @@ int skipffn_gather_rows(const void* src, void* dst, int64_t T, int64_t row_bytes
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];
  * [2] 1/rms f32 [R]; [3] gate bf16 [R, I]; [4] up bf16 [R, I];
- * [5] silu(gate)*up bf16 [R, I].  `offsets` is a HOST array of 6. */
+ * [5] silu(gate)*up bf16 [R, I]; [6] normalised rows transposed, bf16 [C, ld] with
+ * ld = R_max rounded up to a multiple of 8 (columns >= R are zero).
+ * `offsets` is a HOST array of 7. */
 int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets);
 
 /* ---- diagnostics ---------------------------------------------------------- */

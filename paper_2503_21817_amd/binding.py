@@ -130,7 +130,7 @@ def skipffn_backward_workspace_bytes(R_max, C, I) -> int:
 
 
 def skipffn_saved_layout(R_max, C, I):
-    arr = (c_size_t * 6)()
+    arr = (c_size_t * 7)()
     _check(lib().skipffn_saved_layout(R_max, C, I, arr), "skipffn_saved_layout")
     return list(arr)
 
@@ -218,4 +218,6 @@ class SkipFFNBuffers:
             "G": sect(off[3], R * I * 2, torch.bfloat16, (R, I)),
             "U": sect(off[4], R * I * 2, torch.bfloat16, (R, I)),
             "H": sect(off[5], R * I * 2, torch.bfloat16, (R, I)),
+            "xnT": sect(off[6], C * ((self.R_max + 7) // 8 * 8) * 2, torch.bfloat16,
+                        (C, (self.R_max + 7) // 8 * 8)),
         }

@@ -56,7 +56,9 @@ int choose_splits(int tiles, int ktiles) {
     return best;
 }
 
-struct SavedLayout { size_t off[6]; size_t total; };
+inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
+
+struct SavedLayout { size_t off[7]; size_t total; };
 SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
     SavedLayout L;
     size_t o = 0;
@@ -66,6 +68,7 @@ SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
     L.off[3] = o; o += align_up((size_t)R * I * 2);
     L.off[4] = o; o += align_up((size_t)R * I * 2);
     L.off[5] = o; o += align_up((size_t)R * I * 2);
+    L.off[6] = o; o += align_up((size_t)C * ld_transposed(R) * 2);
     L.total = o;
     return L;
 }
@@ -80,8 +83,6 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     w.total = o;
     return w;
 }
-
-inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
 
 struct BwdWs { size_t dy, dyT, dg, du, partial, total; };
 BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
@@ -220,7 +221,7 @@ size_t skipffn_saved_bytes(int64_t R_max, int64_t C, int64_t I) {
 int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets) {
     if (R_max < 0 || C <= 0 || I <= 0 || offsets == nullptr) return SKIPFFN_EINVAL;
     SavedLayout L = saved_layout(R_max, C, I);
-    for (int i = 0; i < 6; ++i) offsets[i] = L.off[i];
+    for (int i = 0; i < 7; ++i) offsets[i] = L.off[i];
     return SKIPFFN_OK;
 }
 size_t skipffn_forward_workspace_bytes(int64_t R_max, int64_t C, int64_t I, int has_saved) {
@@ -268,7 +269,7 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
 
     FwdWs W = fwd_ws(Rb, C, I, saved != nullptr);
     char* ws = static_cast<char*>(workspace);
-    bf16_t *xrows = nullptr, *xn, *G = nullptr, *U = nullptr, *H;
+    bf16_t *xrows = nullptr, *xn, *xnT = nullptr, *G = nullptr, *U = nullptr, *H;
     float* rstd;
     if (saved != nullptr) {
         SavedLayout L = saved_layout(Rb, C, I);
@@ -279,6 +280,7 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         G = reinterpret_cast<bf16_t*>(sv + L.off[3]);
         U = reinterpret_cast<bf16_t*>(sv + L.off[4]);
         H = reinterpret_cast<bf16_t*>(sv + L.off[5]);
+        xnT = reinterpret_cast<bf16_t*>(sv + L.off[6]);
     } else {
         xn = reinterpret_cast<bf16_t*>(ws + W.xn);
         rstd = reinterpret_cast<float*>(ws + W.rstd);
@@ -290,6 +292,11 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
     e = launch_gather_rmsnorm(static_cast<const bf16_t*>(hidden), idx, (int)Rb, r_dev, (int)C, eps,
                               static_cast<const bf16_t*>(rms_gain), xrows, xn, rstd, s);
     if (e != hipSuccess) return hip_fail(e);
+    if (xnT != nullptr) {   // K-contiguous copy of the normalised rows for the dW_gate / dW_up GEMMs
+        e = launch_gather_transpose(xn, (int)C, nullptr, (int)Rb, r_dev, nullptr, xnT,
+                                    (int)ld_transposed(Rb), s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
 
     // (3) gate/up GEMM + SiLU*mul
     {
@@ -390,6 +397,7 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     const bf16_t* G = reinterpret_cast<const bf16_t*>(sv + L.off[3]);
     const bf16_t* U = reinterpret_cast<const bf16_t*>(sv + L.off[4]);
     const bf16_t* H = reinterpret_cast<const bf16_t*>(sv + L.off[5]);
+    const bf16_t* xnT = reinterpret_cast<const bf16_t*>(sv + L.off[6]);
     BwdWs W = bwd_ws(Rb, C, I);
     char* ws = static_cast<char*>(workspace);
     bf16_t* dY = reinterpret_cast<bf16_t*>(ws + W.dy);
@@ -424,16 +432,18 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         profile_mark_end(KC_GEMM_DH_DWDOWN, s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn : one launch, two problems
+    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn : one launch, two problems.  Each is
+    // computed as (xn^T)[C, R] * dG[R, I] -> [C, I] with the K-contiguous copy of xn as the
+    // 4-fragment operand, and written transposed by the epilogue.
     {
         GemmArgs a{};
-        a.M = (int)I; a.N = (int)C; a.K = (int)Rb; a.k_dev = r_dev;
-        a.A0 = dG; a.A1 = dU; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
-        a.B0 = xn; a.ldb = (int)C; a.b_bytes = (uint32_t)(Rb * C * 2);
+        a.M = (int)C; a.N = (int)I; a.K = (int)Rb; a.k_dev = r_dev;
+        a.A0 = xnT; a.lda = ldT; a.a_bytes = (uint32_t)(C * (int64_t)ldT * 2);
+        a.B0 = dG; a.B1 = dU; a.ldb = (int)I; a.b_bytes = (uint32_t)(Rb * I * 2);
         a.pairs = 1; a.splits = 1; a.batch = 2;
         a.out0 = dw_gate; a.out1 = dw_up; a.ldo = (int)C; a.out_f32 = f32; a.accumulate = accum;
         profile_mark_begin(KC_GEMM_DW_GATE_UP, s);
-        e = launch_gemm(false, false, EPI_STORE, a, s);
+        e = launch_gemm(true, false, EPI_STORE_T, a, s);
         profile_mark_end(KC_GEMM_DW_GATE_UP, s);
         if (e != hipSuccess) return hip_fail(e);
     }

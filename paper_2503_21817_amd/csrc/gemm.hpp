@@ -46,7 +46,8 @@ enum EpiKind : int {
     EPI_STORE = 1,         // out0 [M,N] bf16 or fp32, overwrite or accumulate
     EPI_PARTIAL = 2,       // fp32 partial[z][M][N]
     EPI_RESID_SCATTER = 3, // out0[idx[m]][n] = bf16(res[idx[m]][n] + acc)
-    EPI_SWIGLU_BWD = 4     // acc = dH; e0=G, e1=U -> out0 = dG, out1 = dU (bf16)
+    EPI_SWIGLU_BWD = 4,    // acc = dH; e0=G, e1=U -> out0 = dG, out1 = dU (bf16)
+    EPI_STORE_T = 5        // like EPI_STORE, but the result is written transposed: out0[n][m] (ldo = M extent)
 };
 
 struct GemmArgs {
@@ -57,7 +58,8 @@ struct GemmArgs {
     const bf16_t* B0; const bf16_t* B1; int ldb; uint32_t b_bytes;
     int pairs;                   // 1, or 2: K runs over (A0,B0) then (A1,B1)
     int splits;                  // split-K factor
-    int batch;                   // 1, or 2 independent problems sharing B: (A0 -> out0), (A1 -> out1); pairs == 1
+    int batch;                   // 1, or 2 independent problems: (A0 -> out0), (A1 -> out1) sharing B; for
+                                 // EPI_STORE_T (B0 -> out0), (B1 -> out1) sharing A.  pairs == 1
     int tiles_m, tiles_n;
     void* out0; void* out1; void* out2; int ldo;
     const bf16_t* e0; const bf16_t* e1; int lde;
@@ -167,7 +169,7 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     const bool second = P.batch == 2 && z >= P.splits;
     if (second) {
         z -= P.splits;
-        P.A0 = P.A1;
+        if (EPI == EPI_STORE_T) P.B0 = P.B1; else P.A0 = P.A1;
         P.out0 = P.out1;
     }
 
@@ -327,9 +329,11 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
                         // B fragment first: the accumulator then holds, per lane, one row m of
-                        // C and four consecutive columns n per register quad (see the epilogue)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            bfr[s][nt], af[s][mt], acc[mt][nt], 0, 0, 0);
+                        // C and four consecutive columns n per register quad (see the epilogue).
+                        // EPI_STORE_T wants the opposite (one column n, four consecutive rows m).
+                        acc[mt][nt] = (EPI == EPI_STORE_T)
+                            ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mt], bfr[s][nt], acc[mt][nt], 0, 0, 0)
+                            : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][nt], af[s][mt], acc[mt][nt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         };
         auto phase_barrier = [&]() {
@@ -370,6 +374,69 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
             phase_barrier();
         }
         if (wm == 0) phase_barrier();                     // balances group 1's extra barrier
+    }
+
+    if (EPI == EPI_STORE_T) {
+        // ---- transposed epilogue: out0[n][m] = C[m][n] ---------------------------------
+        // With the A fragment first, acc[mt][nt][r] is C[row][col] with
+        //   row = m0 + wm*128 + mt*32 + 8*(r/4) + 4*(lane/32) + r%4,  col = n0 + wn*64 + nt*32 + lane%32:
+        // a register quad is four consecutive m of one column n, i.e. 16 contiguous bytes of
+        // the transposed result.  Per pass nt all eight waves stage 128 columns n x 256 rows m
+        // (fp32) in LDS; each thread then moves row-contiguous chunks of 8.
+        constexpr int T_STRIDE = 256 * 4 + 16;
+        static_assert(128 * T_STRIDE <= GEMM_LDS_BYTES, "staging must fit in LDS");
+        const int hh = lane >> 5;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            if (nt) __syncthreads();                 // previous pass fully read back
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 v = {acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2],
+                               acc[mt][nt][4 * g + 3]};
+                    const int srow = wn * 32 + (lane & 31);
+                    const int scol = wm * 128 + mt * 32 + 8 * g + 4 * hh;
+                    *reinterpret_cast<f32x4*>(smem + srow * T_STRIDE + scol * 4) = v;
+                }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int cid = t + 512 * i;
+                const int r = cid >> 5, c = cid & 31;          // staged row (a column n of C), chunk
+                const int ncol = n0 + (r >> 5) * 64 + nt * 32 + (r & 31);
+                const int mrow = m0 + c * 8;
+                if (ncol >= P.N || mrow >= Meff) continue;
+                const int swap = (c >> 3) & 1;
+                const char* src = smem + r * T_STRIDE + c * 32;
+                f32x4 a = *reinterpret_cast<const f32x4*>(src + (swap ? 16 : 0));
+                f32x4 b = *reinterpret_cast<const f32x4*>(src + (swap ? 0 : 16));
+                f32x4 lo = swap ? b : a, hi = swap ? a : b;
+                const uint32_t o = (uint32_t)ncol * (uint32_t)P.ldo + (uint32_t)mrow;
+                if (P.out_f32) {
+                    f32x4* O = reinterpret_cast<f32x4*>(static_cast<float*>(P.out0) + o);
+                    if (P.accumulate) { lo += O[0]; hi += O[1]; }
+                    O[0] = lo;
+                    O[1] = hi;
+                } else {
+                    u32x4* O = reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o);
+                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    if (P.accumulate) {
+                        u32x4 old = *O;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            v[2 * k] += bf16lo_to_f32(old[k]);
+                            v[2 * k + 1] += bf16hi_to_f32(old[k]);
+                        }
+                    }
+                    u32x4 pk;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) pk[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
+                    *O = pk;
+                }
+            }
+        }
+        return;
     }
 
     // ---- epilogue --------------------------------------------------------------

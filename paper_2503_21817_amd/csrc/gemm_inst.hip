@@ -16,7 +16,7 @@ hipError_t gemm_init() {
     if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
-    if ((e = set_lds_limit<false, false, EPI_STORE>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, false, EPI_STORE_T>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_STORE>()) != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, false, EPI_STORE>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
@@ -60,7 +60,7 @@ hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s
     if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER>(a, s);
     if (a_kc && !b_kc && epi == EPI_SWIGLU_BWD) return launch_one<true, false, EPI_SWIGLU_BWD>(a, s);
     if (a_kc && !b_kc && epi == EPI_PARTIAL) return launch_one<true, false, EPI_PARTIAL>(a, s);
-    if (!a_kc && !b_kc && epi == EPI_STORE) return launch_one<false, false, EPI_STORE>(a, s);
+    if (a_kc && !b_kc && epi == EPI_STORE_T) return launch_one<true, false, EPI_STORE_T>(a, s);
     if (a_kc && !b_kc && epi == EPI_STORE) return launch_one<true, false, EPI_STORE>(a, s);
     return hipErrorInvalidValue;
 }

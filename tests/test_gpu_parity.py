@@ -116,6 +116,10 @@ def test_forward_stage_by_stage(w, gain):
     assert rel_l2(f64_of(sv["xn"]), ref["xn"]) < 3e-3          # one bf16 rounding: 2^-9 rms
     for k in ("G", "U", "H"):
         assert rel_l2(f64_of(sv[k]), ref[k]) < REL_L2_TOL, k
+    # the transposed copy of the normalised rows is exact, its padding columns are zero
+    xnT = bits_of(sv["xnT"])
+    assert np.array_equal(xnT[:, :R], bits_of(sv["xn"]).T)
+    assert not xnT[:, R:].any()
     got = bits_of(out)
     skipped = p.mask != 0
     assert np.array_equal(got[skipped], p.hidden[skipped])      # bitwise passthrough
