@@ -26,6 +26,16 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
+# Bytes per launch that the L2s exchanged with the fabric / HBM for configuration 2, forward +
+# backward: rocprofv3 --pmc FETCH_SIZE (x 2.0, calibrated with a copy kernel) + WRITE_SIZE, from
+# profiles/bench_cfg2_fwd_bwd_hbm_traffic_and_mfma_counters.md.  Counters cannot be read from
+# inside this process, so the figure is the profiled one for the same launch configuration.
+MEASURED_TRAFFIC_CFG2_FWD_BWD = {
+    "gemm_gate_up_swiglu": 685.0e6, "gemm_down": 334.6e6, "gemm_dh_swiglu_bwd+dw_down": 1027.5e6,
+    "gemm_dw_gate_up": 741.7e6, "gemm_dxn": 710.9e6, "gather_rmsnorm": 36.5e6,
+    "resid_scatter": 72.4e6, "rmsnorm_bwd_scatter": 157.0e6, "gather_rows": 30.2e6,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -52,7 +62,7 @@ def kernel_work(name, R, T, C, I, dw_bytes):
         "compact": ("hbm", T + 4 * R),
         "gather_rmsnorm": ("hbm", 2 * rc * 2 + 4 * R),
         "resid_scatter": ("hbm", 2 * rc * 2),
-        "gather_rows": ("hbm", 2 * rc * 2),
+        "gather_rows": ("hbm", 2.5 * rc * 2),                     # row gather + transposed copy
         "rmsnorm_bwd_scatter": ("hbm", rc * (2 + 2 + 4 + 2)),
         "passthrough_copy": ("hbm", 2 * (T - R) * C * 2),
     }
@@ -192,7 +202,8 @@ def main():
     else:
         achieved, peak, unit = amount / dom_avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = {"kernel": dom, "bound": kind, "achieved": round(achieved, 2), "peak": peak,
-                "unit": unit, "frac": round(achieved / peak, 4), "traffic": None,
+                "unit": unit, "frac": round(achieved / peak, 4),
+                "traffic": (MEASURED_TRAFFIC_CFG2_FWD_BWD.get(dom) if (args.config == 2 and bwd) else None),
                 "avg_launch_ms": kernels[dom]["avg_ms"]}
     gemm_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k.startswith("gemm_"))
 
