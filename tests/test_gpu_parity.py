@@ -235,3 +235,36 @@ def test_skip_kv_cache_row_gather():
     B.skipffn_gather_rows(src, dst, torch.from_numpy(idx).cuda(), R)
     torch.cuda.synchronize()
     assert np.array_equal(bits_of(dst), O.kv_skip_cache(cache, m))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_shapes_forward_backward(seed):
+    """Seeded random shapes: odd multiples of 8 for C and I, ragged R, one to three
+    sequences; both R given by the host and R read on the device."""
+    rng = np.random.default_rng(1000 + seed)
+    C = 8 * int(rng.integers(8, 90))
+    I = 8 * int(rng.integers(8, 200))
+    nseq = int(rng.integers(1, 4))
+    vis = [int(rng.integers(1, 400)) for _ in range(nseq)]
+    txt = [int(rng.integers(0, 30)) for _ in range(nseq)]
+    keep = [int(rng.integers(0, v + 1)) for v in vis]
+    w = W.small(C=C, I=I, visual=vis, text=txt, keep=keep, seed=50 + seed, name=f"rand{seed}")
+    print(f"random shape {seed}: T={w.T} R={w.R} C={C} I={I}", flush=True)
+    if w.R == 0:
+        pytest.skip("empty retained set is covered elsewhere")
+    p = Problem(w, unit_gain=False, with_gain_tensor=bool(seed & 1))
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    idx = fo["idx"]
+    sk = p.mask != 0
+    for r_host in (True, False):
+        out, bufs = gpu_forward(p, R_host=r_host, inplace=bool(seed & 2))
+        got = bits_of(out)
+        assert np.array_equal(got[sk], p.hidden[sk])
+        assert rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx])) < REL_L2_TOL
+        gh, dw = gpu_backward(p, bufs, R_host=r_host, inplace=bool(seed & 2))
+        gb = bits_of(gh)
+        assert np.array_equal(gb[sk], p.grad[sk])
+        assert rel_l2(O.bf16_bits_to_f64(gb[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
+        for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+            assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, (k, r_host)
