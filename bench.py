@@ -42,7 +42,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..4 (token mix and layer shape)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
+                         "backward 32..1)")
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact"],
+                    help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
+                         "tokens at the configuration's fixed T; compact: the mask compaction alone at "
+                         "T = 2^16 .. 2^26.  The JSON line then carries a 'sweep' array")
     ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
@@ -99,11 +105,114 @@ def cpu_baseline(w, passes, target_s):
     if len(lens) > 1 and dt1 < target_s / 2:
         nseq = int(min(len(lens), max(1, target_s // max(dt1, 1e-3))))
     dt, n, R = (dt1, n1, R1) if nseq == 1 else run(nseq)
-    flops = skipffn_flops(R, w.C, w.I, passes == "fwd+bwd")
+    reps = 1
+    if nseq == len(lens) and dt < target_s / 2:
+        # the whole batch is quicker than the target: repeat it
+        extra = int(min(10, target_s // max(dt, 1e-3)))
+        for _ in range(extra):
+            dt += run(nseq)[0]
+        reps += extra
+    flops = reps * skipffn_flops(R, w.C, w.I, passes == "fwd+bwd")
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
             "sample": f"first {nseq} of {len(lens)} sequences ({n} tokens, {R} retained), "
-                      f"{passes}, fp64 numpy, {dt:.1f} s",
-            "seconds": dt, "retained_tokens_per_s": R / dt}
+                      f"{'one layer, ' if w.layers > 1 else ''}{passes}, fp64 numpy, {reps} pass(es), {dt:.1f} s",
+            "seconds": dt, "retained_tokens_per_s": reps * R / dt}
+
+
+def _time_steps(torch, fn, warmup, steps):
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        fn(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def retention_sweep(torch, B, W, w, bwd, args):
+    """Step time against the retained share of the visual tokens at fixed T (Section 5.2's
+    cost model is linear in the retained count): one entry per fraction and a least-squares
+    line  ms = intercept + slope * R."""
+    from dataclasses import replace
+    from paper_2503_21817_amd.flopmodel import skipffn_flops
+
+    def dev_bf16(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    T, C, I = w.T, w.C, w.I
+    hidden0 = dev_bf16(W.make_hidden(w))
+    grad0 = dev_bf16(W.make_grad(w))
+    wg, wu, wd = (dev_bf16(a) for a in W.make_weights(w))
+    dws = [torch.empty(shape, dtype=torch.bfloat16, device="cuda") for shape in ((I, C), (I, C), (C, I))]
+    bufs = B.SkipFFNBuffers(T, T, C, I, training=bwd)
+    ncopy = 8
+    hiddens = [hidden0.clone() for _ in range(ncopy)]
+    grads = [grad0.clone() for _ in range(ncopy)]
+    rows = []
+    for frac in (0.0, 0.125, 0.25, 0.5, 1.0):
+        wf = replace(w, keep=[int(round(frac * v)) for v in w.visual], text=list(w.text))
+        # fraction 0 also drops the text tokens from the FFN: the empty-set path of the block
+        mask_np = W.make_mask(wf)
+        if frac == 0.0:
+            mask_np[:] = 1
+        mask = torch.from_numpy(mask_np).cuda()
+        R = int((mask_np == 0).sum())
+
+        def step(i):
+            h = hiddens[i % ncopy]
+            B.skipffn_compact(mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+            B.skipffn_forward(h, h, bufs.idx, R, wg, wu, wd, eps=w.eps, saved=bufs.saved,
+                              workspace=bufs.fwd_ws)
+            if bwd:
+                g = grads[i % ncopy]
+                B.skipffn_backward(g, g, bufs.idx, R, wg, wu, wd, bufs.saved, *dws, eps=w.eps,
+                                   workspace=bufs.bwd_ws)
+
+        ms = _time_steps(torch, step, args.warmup, args.steps)
+        fl = skipffn_flops(R, C, I, bwd)
+        rows.append({"retained_fraction_of_visual": frac, "R": R, "ms_per_step": round(ms, 4),
+                     "tflops": round(fl / (ms * 1e-3) / 1e12, 1)})
+    Rs = np.array([r["R"] for r in rows], dtype=np.float64)
+    ms = np.array([r["ms_per_step"] for r in rows])
+    slope, intercept = np.polyfit(Rs, ms, 1)
+    return {"metric": "Skip-FFN step time against retained count", "unit": "ms", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"{w.name}: T={T} fixed, C={C}, I={I}, 1 layer, {args.passes}, "
+                                   "in place"},
+            "sweep": rows, "fit_ms": {"intercept": round(float(intercept), 4),
+                                      "per_1000_retained": round(float(slope) * 1e3, 4)}}
+
+
+def compact_sweep(torch, B, args):
+    """The mask compaction alone, 25 % retained at seeded-uniform positions: algorithmic
+    bytes T (mask) + 4 R (index list) per launch against HIP-event time."""
+    rows = []
+    for lg in (13, 16, 20, 24, 26):
+        T = 1 << lg
+        g = torch.Generator(device="cuda")
+        g.manual_seed(77 + lg)
+        mask = (torch.rand(T, generator=g, device="cuda") >= 0.25).to(torch.uint8)
+        idx = torch.empty(T, dtype=torch.int32, device="cuda")
+        nret = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(max(B.skipffn_compact_workspace_bytes(T), 16), dtype=torch.uint8, device="cuda")
+        for _ in range(args.warmup):
+            B.skipffn_compact(mask, idx, nret, None, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.skipffn_compact(mask, idx, nret, None, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        R = int(nret.item())
+        assert R == int((mask == 0).sum().item())
+        gbs = (T + 4 * R) / (ms * 1e-3) / 1e9
+        rows.append({"T": T, "R": R, "us": round(ms * 1e3, 2), "gbs": round(gbs, 1),
+                     "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)})
+    return {"metric": "mask compaction bandwidth", "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "mask compaction, 25 % retained, T = 2^13 .. 2^26"}, "sweep": rows}
 
 
 def main():
@@ -125,7 +234,14 @@ def main():
 
     w = W.config(args.config)
     bwd = args.passes == "fwd+bwd"
+    if args.sweep == "compact":
+        print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "retention":
+        print(json.dumps(retention_sweep(torch, B, W, w, bwd, args)))
+        return
     T, R, C, I = w.T, w.R, w.C, w.I
+    L = w.layers
 
     def dev_bf16(bits):
         return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
@@ -133,11 +249,24 @@ def main():
     mask = torch.from_numpy(W.make_mask(w)).cuda()
     hidden0 = dev_bf16(W.make_hidden(w))
     grad0 = dev_bf16(W.make_grad(w))
-    wg, wu, wd = (dev_bf16(a) for a in W.make_weights(w))
+    if L == 1:
+        weights = [tuple(dev_bf16(a) for a in W.make_weights(w))]
+        data = "synthetic"
+    else:
+        # 32 layers of independent N(0, 0.02) weights, drawn on the device (seeded): the host
+        # generator of the parity tests would hold the GPU idle for minutes
+        gen = torch.Generator(device="cuda")
+        weights = []
+        for l in range(L):
+            gen.manual_seed(2000 + w.cfg * 100 + l)
+            weights.append(tuple(
+                (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * 0.02)
+                .to(torch.bfloat16) for shape in ((I, C), (I, C), (C, I))))
+        data = "synthetic (weights drawn on the device)"
     bufs = B.SkipFFNBuffers(T, R, C, I, training=bwd)
-    dwg = torch.empty((I, C), dtype=torch.bfloat16, device="cuda")
-    dwu = torch.empty((I, C), dtype=torch.bfloat16, device="cuda")
-    dwd = torch.empty((C, I), dtype=torch.bfloat16, device="cuda")
+    saved = [bufs.saved] + [torch.empty_like(bufs.saved) for _ in range(L - 1)] if bwd else [None] * L
+    dws = [tuple(torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+                 for shape in ((I, C), (I, C), (C, I))) for _ in range(L)] if bwd else []
 
     # The block runs in place (skipped rows are never touched); rotate through
     # fresh copies of the input so values do not drift from step to step.
@@ -148,12 +277,16 @@ def main():
     def step(i):
         h = hiddens[i % ncopy]
         B.skipffn_compact(mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
-        B.skipffn_forward(h, h, bufs.idx, R, wg, wu, wd, eps=w.eps, saved=bufs.saved,
-                          workspace=bufs.fwd_ws)
+        for l in range(L):
+            wg, wu, wd = weights[l]
+            B.skipffn_forward(h, h, bufs.idx, R, wg, wu, wd, eps=w.eps, saved=saved[l],
+                              workspace=bufs.fwd_ws)
         if bwd:
             g = grads[i % ncopy]
-            B.skipffn_backward(g, g, bufs.idx, R, wg, wu, wd, bufs.saved, dwg, dwu, dwd,
-                               eps=w.eps, workspace=bufs.bwd_ws)
+            for l in reversed(range(L)):
+                wg, wu, wd = weights[l]
+                B.skipffn_backward(g, g, bufs.idx, R, wg, wu, wd, saved[l], *dws[l],
+                                   eps=w.eps, workspace=bufs.bwd_ws)
 
     for i in range(args.warmup):
         step(i)
@@ -207,17 +340,17 @@ def main():
                 "avg_launch_ms": kernels[dom]["avg_ms"]}
     gemm_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k.startswith("gemm_"))
 
-    flops = skipffn_flops(R, C, I, bwd)
+    flops = L * skipffn_flops(R, C, I, bwd)
     tflops = flops / (ms_step * 1e-3) / 1e12
     rec = {
         "metric": "retained-token FFN fwd+bwd TFLOP/s" if bwd else "retained-token FFN fwd TFLOP/s",
         "value": round(tflops, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": "bf16", "data": data,
         "config": {"workload": f"{w.name}: T={T} tokens, R={R} retained, C={C}, I={I}, "
-                               f"1 layer, {args.passes}, in place",
-                   "T": T, "R": R, "C": C, "I": I, "passes": args.passes},
+                               f"{L} layer{'s' if L > 1 else ''}, {args.passes}, in place",
+                   "T": T, "R": R, "C": C, "I": I, "layers": L, "passes": args.passes},
         "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "gemm_only_tflops": round(flops / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms > 0 else None,
         "effective_tokens_per_s": round(T / (ms_step * 1e-3)),

@@ -28,15 +28,17 @@ __device__ __forceinline__ float bf16lo_to_f32(uint32_t packed) {
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t packed) {
     return __uint_as_float(packed & 0xffff0000u);
 }
-// round to nearest even; NaN stays a (quiet) NaN
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    const uint32_t quiet = (u >> 16) | 0x0040u;
-    return (bf16_t)(((u & 0x7fffffffu) > 0x7f800000u) ? quiet : rounded);   // select, no branch
-}
+// round to nearest even; NaN stays a (quiet) NaN.  gfx950 converts in hardware
+// (v_cvt_pk_bf16_f32, two values per instruction): the integer formulation costs about ten
+// VALU instructions per element, which made the GEMM epilogues VALU-bound.
+typedef __attribute__((ext_vector_type(2))) float f32x2_cvt;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_cvt;
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    const f32x2_cvt v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_cvt));
+}
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    return (bf16_t)(pack_bf16x2(f, 0.0f) & 0xffffu);
 }
 
 // ---- wave reductions --------------------------------------------------------

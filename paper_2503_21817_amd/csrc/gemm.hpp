@@ -131,6 +131,17 @@ __device__ __forceinline__ float sigmoid_f(float g) {
 // s_waitcnt lgkmcnt(0) only
 #define SKIPFFN_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for vmcnt(0),
+// i.e. until every global store this wave has issued is acknowledged (microseconds per
+// epilogue pass); the epilogues hand data from wave to wave through LDS alone, so their
+// stores may stay in flight across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    SKIPFFN_WAIT_LGKMCNT0();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // blockIdx.x -> (tile m, tile n, split).  Workgroups are dealt round-robin to the
 // 8 XCDs, each with its own L2: the remap gives every XCD a contiguous range of a
 // logical order in which 32 consecutive tiles form a PANEL_M x (32 / PANEL_M)
@@ -388,7 +399,7 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
         const int hh = lane >> 5;
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) {
-            if (nt) __syncthreads();                 // previous pass fully read back
+            if (nt) lds_barrier();                   // previous pass fully read back
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
@@ -399,7 +410,7 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
                     const int scol = wm * 128 + mt * 32 + 8 * g + 4 * hh;
                     *reinterpret_cast<f32x4*>(smem + srow * T_STRIDE + scol * 4) = v;
                 }
-            __syncthreads();
+            lds_barrier();
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int cid = t + 512 * i;
@@ -448,7 +459,8 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     // row group (wm) dumps its 32 x 256 fp32 slice as 16-byte vectors, and after a
     // barrier each thread takes row-contiguous chunks of 8 columns, applies the
     // epilogue arithmetic and moves 16 bytes per global access.  Two staging
-    // buffers alternate, so one barrier per pass suffices.
+    // buffers alternate, so one barrier per pass suffices; the barrier orders LDS traffic
+    // only, so the stores of one pass overlap the staging of the next.
     constexpr int SLICE_COLS = (EPI == EPI_SWIGLU) ? 128 : 256;       // per staged matrix
     constexpr int SLICE_STRIDE = SLICE_COLS * 4 + 16;                   // bytes; +16 spreads rows over banks
     constexpr int SLICE_MATS = (EPI == EPI_SWIGLU) ? 2 : 1;             // G and U
@@ -458,6 +470,26 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     const int tg = t & 255;                       // thread index inside the row group
     constexpr int CHUNKS_PER_ROW = SLICE_COLS / 8;
     constexpr int CHUNKS_PER_THREAD = EPI_ROWS * CHUNKS_PER_ROW / 256;
+
+    // EPI_SWIGLU_BWD reads G and U next to the accumulator: those 16-byte loads are issued one
+    // pass ahead (and ahead of the previous pass's stores in the in-order vmcnt queue), so
+    // their latency hides behind the staging of the pass before.
+    u32x4 pre_g[2][CHUNKS_PER_THREAD], pre_u[2][CHUNKS_PER_THREAD];
+    auto prefetch_gu = [&](int mt) {
+        if (EPI != EPI_SWIGLU_BWD) return;
+#pragma unroll
+        for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
+            const int cid = tg + 256 * i;
+            const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
+            const int row = m0 + wm * 128 + mt * 32 + r;
+            const int col = n0 + c * 8;
+            if (row >= Meff || col >= P.N) continue;
+            const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
+            pre_g[mt & 1][i] = *reinterpret_cast<const u32x4*>(P.e0 + o);
+            pre_u[mt & 1][i] = *reinterpret_cast<const u32x4*>(P.e1 + o);
+        }
+    };
+    prefetch_gu(0);
 
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt) {
@@ -475,7 +507,8 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
                 *reinterpret_cast<f32x4*>(sbuf + mat * EPI_ROWS * SLICE_STRIDE +
                                           (lane & 31) * SLICE_STRIDE + col * 4) = v;
             }
-        __syncthreads();
+        lds_barrier();
+        if (mt + 1 < 4) prefetch_gu(mt + 1);
         // ---- row-contiguous chunks of 8 columns
 #pragma unroll
         for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
@@ -560,8 +593,8 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
                 *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o) = pk;
             } else if (EPI == EPI_SWIGLU_BWD) {
                 const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
-                u32x4 gq = *reinterpret_cast<const u32x4*>(P.e0 + o);
-                u32x4 uq = *reinterpret_cast<const u32x4*>(P.e1 + o);
+                const u32x4 gq = pre_g[mt & 1][i];
+                const u32x4 uq = pre_u[mt & 1][i];
                 u32x4 dgq, duq;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
