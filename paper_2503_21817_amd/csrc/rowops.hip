@@ -1,14 +1,15 @@
-// Memory-bound row kernels of the Skip-FFN block: one wavefront per token row,
-// 16-byte accesses, fp32 arithmetic.  Rows are addressed through the retained
-// index list, so only the R retained rows are touched (Section 4.2: skipped
-// tokens keep their residual and see no FFN work).
+// Memory-bound row kernels of the Skip-FFN block: 16-byte accesses, fp32 arithmetic.
+// Rows are addressed through the retained index list, so only the R retained rows are
+// touched (Section 4.2: skipped tokens keep their residual and see no FFN work).
+// Kernels that reduce over a row give the row to one 256-thread workgroup (R is a few
+// thousand at most, so a wavefront per row would leave most of the chip without work in
+// flight); purely elementwise ones run one thread per 16-byte chunk.
 #include "kernels.hpp"
 
 namespace skipffn {
 
-constexpr int ROW_THREADS = 256;              // 4 rows per block
-constexpr int ROWS_PER_BLOCK = ROW_THREADS / 64;
-constexpr int RMS_MAXV = 16;                  // register-resident row up to C = 64*8*16 = 8192
+constexpr int ROW_THREADS = 256;
+constexpr int RMS_MAXV = 4;                   // register-resident row up to C = 256*8*4 = 8192
 
 __device__ __forceinline__ void unpack8(const u32x4& v, float* f) {
 #pragma unroll
@@ -23,6 +24,13 @@ __device__ __forceinline__ u32x4 pack8(const float* f) {
     for (int j = 0; j < 4; ++j) v[j] = pack_bf16x2(f[2 * j], f[2 * j + 1]);
     return v;
 }
+// sum over the 256 threads of a workgroup (one call per kernel: `red` is not reused)
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
 
 // ---- gather + RMSNorm -------------------------------------------------------------
 // n(x) = x * rsqrt(mean(x^2) + eps) * gain for the rows idx[r]; x is read once
@@ -32,10 +40,11 @@ __global__ __launch_bounds__(ROW_THREADS) void gather_rmsnorm_kernel(
     const bf16_t* __restrict__ hidden, const int32_t* __restrict__ idx, int Rbound,
     const int32_t* __restrict__ r_dev, int C, float eps, const bf16_t* __restrict__ gain,
     bf16_t* __restrict__ xrows, bf16_t* __restrict__ xn, float* __restrict__ rstd_out) {
+    __shared__ float red[4];
     const int R = effective_rows(Rbound, r_dev);
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
-    if (r >= R) return;
+    const int tid = threadIdx.x;
+    const int r = blockIdx.x;
+    if (r >= R) return;                       // the whole workgroup leaves together
     const int chunks = C >> 3;
     const u32x4* src = reinterpret_cast<const u32x4*>(hidden + (int64_t)idx[r] * C);
     const u32x4* gsrc = reinterpret_cast<const u32x4*>(gain);
@@ -47,7 +56,7 @@ __global__ __launch_bounds__(ROW_THREADS) void gather_rmsnorm_kernel(
     if (IN_REGS) {
 #pragma unroll
         for (int v = 0; v < RMS_MAXV; ++v) {
-            int c = lane + 64 * v;
+            int c = tid + ROW_THREADS * v;
             if (c < chunks) {
                 held[v] = src[c];
                 float f[8];
@@ -57,16 +66,16 @@ __global__ __launch_bounds__(ROW_THREADS) void gather_rmsnorm_kernel(
             }
         }
     } else {
-        for (int c = lane; c < chunks; c += 64) {
+        for (int c = tid; c < chunks; c += ROW_THREADS) {
             float f[8];
             unpack8(src[c], f);
 #pragma unroll
             for (int j = 0; j < 8; ++j) ss += f[j] * f[j];
         }
     }
-    ss = wave_sum(ss);
+    ss = block_sum(ss, red);
     const float rstd = 1.0f / sqrtf(ss / (float)C + eps);
-    if (lane == 0) rstd_out[r] = rstd;
+    if (tid == 0) rstd_out[r] = rstd;
 
     auto emit = [&](int c, const u32x4& raw) {
         float f[8];
@@ -86,11 +95,11 @@ __global__ __launch_bounds__(ROW_THREADS) void gather_rmsnorm_kernel(
     if (IN_REGS) {
 #pragma unroll
         for (int v = 0; v < RMS_MAXV; ++v) {
-            int c = lane + 64 * v;
+            int c = tid + ROW_THREADS * v;
             if (c < chunks) emit(c, held[v]);
         }
     } else {
-        for (int c = lane; c < chunks; c += 64) emit(c, src[c]);
+        for (int c = tid; c < chunks; c += ROW_THREADS) emit(c, src[c]);
     }
 }
 
@@ -98,9 +107,9 @@ hipError_t launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* idx, int R
                                  const int32_t* r_dev, int C, float eps, const bf16_t* gain,
                                  bf16_t* xrows, bf16_t* xn, float* rstd, hipStream_t s) {
     if (R <= 0) return hipSuccess;
-    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    dim3 grid(R), block(ROW_THREADS);
     profile_mark_begin(KC_GATHER_RMSNORM, s);
-    if (C <= 64 * 8 * RMS_MAXV)
+    if (C <= ROW_THREADS * 8 * RMS_MAXV)
         hipLaunchKernelGGL(gather_rmsnorm_kernel<true>, grid, block, 0, s, hidden, idx, R, r_dev, C,
                            eps, gain, xrows, xn, rstd);
     else
@@ -112,45 +121,45 @@ hipError_t launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* idx, int R
 
 // ---- split-K reduce + residual + scatter ----------------------------------------------
 // out[idx[r]][c] = bf16( res[idx[r]][c] + sum_z partial[z][r][c] ), summed in z order.
+// One thread per 16-byte chunk of the output.
 __global__ __launch_bounds__(ROW_THREADS) void resid_scatter_kernel(
     const float* __restrict__ partial, int splits, int Rbound, const int32_t* __restrict__ r_dev,
     int C, const int32_t* __restrict__ idx, const bf16_t* res, bf16_t* out, int no_residual) {
     const int R = effective_rows(Rbound, r_dev);
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
-    if (r >= R) return;
     const int chunks = C >> 3;
+    const int64_t g = (int64_t)blockIdx.x * ROW_THREADS + threadIdx.x;
+    const int r = (int)(g / chunks), c = (int)(g - (int64_t)r * chunks);
+    if (r >= R) return;
     const int64_t orow = (int64_t)idx[r] * C;
     const int64_t zstride = (int64_t)Rbound * C;
-    for (int c = lane; c < chunks; c += 64) {
-        float acc[8];
+    float acc[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
-        const float* p = partial + (int64_t)r * C + c * 8;
-        for (int z = 0; z < splits; ++z) {
-            f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride);
-            f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + 4);
+    for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
+    const float* p = partial + (int64_t)r * C + c * 8;
+    for (int z = 0; z < splits; ++z) {
+        f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride);
+        f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                acc[j] += a[j];
-                acc[4 + j] += b[j];
-            }
+        for (int j = 0; j < 4; ++j) {
+            acc[j] += a[j];
+            acc[4 + j] += b[j];
         }
-        if (!no_residual) {
-            float x[8];
-            unpack8(*reinterpret_cast<const u32x4*>(res + orow + c * 8), x);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] += x[j];
-        }
-        *reinterpret_cast<u32x4*>(out + orow + c * 8) = pack8(acc);
     }
+    if (!no_residual) {
+        float x[8];
+        unpack8(*reinterpret_cast<const u32x4*>(res + orow + c * 8), x);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] += x[j];
+    }
+    *reinterpret_cast<u32x4*>(out + orow + c * 8) = pack8(acc);
 }
 
 hipError_t launch_resid_scatter(const float* partial, int splits, int R, const int32_t* r_dev,
                                 int C, const int32_t* idx, const bf16_t* res, bf16_t* out,
                                 int no_residual, hipStream_t s) {
     if (R <= 0) return hipSuccess;
-    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    const int64_t total = (int64_t)R * (C >> 3);
+    dim3 grid((unsigned)((total + ROW_THREADS - 1) / ROW_THREADS)), block(ROW_THREADS);
     profile_mark_begin(KC_RESID_SCATTER, s);
     hipLaunchKernelGGL(resid_scatter_kernel, grid, block, 0, s, partial, splits, R, r_dev, C, idx,
                        res, out, no_residual);
@@ -159,6 +168,7 @@ hipError_t launch_resid_scatter(const float* partial, int splits, int R, const i
 }
 
 // ---- row gather (upstream gradient rows; skip KV-cache of Section 4.3) -----------------
+constexpr int ROWS_PER_BLOCK = ROW_THREADS / 64;   // copy kernels: one wavefront per row
 __global__ __launch_bounds__(ROW_THREADS) void gather_rows_kernel(
     const u32x4* __restrict__ src, u32x4* __restrict__ dst, int64_t row_chunks,
     const int32_t* __restrict__ idx, int Rbound, const int32_t* __restrict__ r_dev) {
@@ -284,10 +294,11 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     int C, const bf16_t* __restrict__ xrows, const float* __restrict__ rstd_in,
     const bf16_t* __restrict__ gain, const bf16_t* __restrict__ dY,
     const int32_t* __restrict__ idx, bf16_t* dX) {
+    __shared__ float red[4];
     const int R = effective_rows(Rbound, r_dev);
-    const int lane = threadIdx.x & 63;
-    const int r = blockIdx.x * ROWS_PER_BLOCK + (threadIdx.x >> 6);
-    if (r >= R) return;
+    const int tid = threadIdx.x;
+    const int r = blockIdx.x;
+    if (r >= R) return;                       // the whole workgroup leaves together
     const int chunks = C >> 3;
     const float rstd = rstd_in[r];
     const int64_t zstride = (int64_t)Rbound * C;
@@ -316,50 +327,52 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     };
     const u32x4* dys = reinterpret_cast<const u32x4*>(dY + (int64_t)r * C);
     u32x4* out = reinterpret_cast<u32x4*>(dX + (int64_t)idx[r] * C);
-    auto emit = [&](int c, const float* d, const float* x, float dot) {
+    auto emit = [&](int c, const float* d, const float* x, const u32x4& dyraw, float dot) {
         float gy[8], o[8];
-        unpack8(dys[c], gy);
+        unpack8(dyraw, gy);
 #pragma unroll
         for (int j = 0; j < 8; ++j) o[j] = gy[j] + rstd * (d[j] - (x[j] * rstd) * dot);
         out[c] = pack8(o);
     };
 
     if (IN_REGS) {
-        // the row (sum of the split-K slabs, and x) is read once and kept in registers
-        constexpr int MAXV = 8;          // C <= 64 * 8 * 8 = 4096
+        // the row (sum of the split-K slabs, x and dY) is read once and kept in registers
+        constexpr int MAXV = 2;          // C <= 256 * 8 * 2 = 4096
         float d[MAXV][8], x[MAXV][8];
+        u32x4 dyraw[MAXV];
         float dot = 0.0f;
 #pragma unroll
         for (int v = 0; v < MAXV; ++v) {
-            int c = lane + 64 * v;
+            int c = tid + ROW_THREADS * v;
             if (c < chunks) {
                 load_dxh(c, d[v]);
                 unpack8(xs[c], x[v]);
+                dyraw[v] = dys[c];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) dot += d[v][j] * (x[v][j] * rstd);
             }
         }
-        dot = wave_sum(dot) / (float)C;
+        dot = block_sum(dot, red) / (float)C;
 #pragma unroll
         for (int v = 0; v < MAXV; ++v) {
-            int c = lane + 64 * v;
-            if (c < chunks) emit(c, d[v], x[v], dot);
+            int c = tid + ROW_THREADS * v;
+            if (c < chunks) emit(c, d[v], x[v], dyraw[v], dot);
         }
     } else {
         float dot = 0.0f;
-        for (int c = lane; c < chunks; c += 64) {
+        for (int c = tid; c < chunks; c += ROW_THREADS) {
             float d[8], x[8];
             load_dxh(c, d);
             unpack8(xs[c], x);
 #pragma unroll
             for (int j = 0; j < 8; ++j) dot += d[j] * (x[j] * rstd);
         }
-        dot = wave_sum(dot) / (float)C;
-        for (int c = lane; c < chunks; c += 64) {
+        dot = block_sum(dot, red) / (float)C;
+        for (int c = tid; c < chunks; c += ROW_THREADS) {
             float d[8], x[8];
             load_dxh(c, d);
             unpack8(xs[c], x);
-            emit(c, d, x, dot);
+            emit(c, d, x, dys[c], dot);
         }
     }
 }
@@ -369,7 +382,7 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int 
                                       const float* rstd, const bf16_t* gain, const bf16_t* dY,
                                       const int32_t* idx, bf16_t* dX, hipStream_t s) {
     if (R <= 0) return hipSuccess;
-    dim3 grid((R + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK), block(ROW_THREADS);
+    dim3 grid(R), block(ROW_THREADS);
     profile_mark_begin(KC_RMSNORM_BWD, s);
     if (C <= 4096)
         hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<true>, grid, block, 0, s, dxn_partial, splits,
