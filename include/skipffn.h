@@ -60,7 +60,9 @@ typedef enum skipffn_status {
 #define SKIPFFN_FLAG_DW_FP32        0x1u  /* backward: dw_* are float32, not bf16 */
 #define SKIPFFN_FLAG_DW_ACCUMULATE  0x2u  /* backward: dw_* += instead of = */
 #define SKIPFFN_FLAG_NO_RESIDUAL    0x4u  /* forward: retained rows get bf16(FFN(x)), not bf16(x + FFN(x)) - a debugging view */
-#define SKIPFFN_FLAG_ALL            0x7u
+#define SKIPFFN_FLAG_BALANCED_SPLIT  0x8u  /* use the balanced K split of the down / dXn GEMMs whenever it applies
+                                             (by default a cost model picks between it, plain split-K and no split) */
+#define SKIPFFN_FLAG_ALL            0xFu
 
 /* ---- step 1: mask -> ascending retained indices -------------------------
  * Section 4.1 decides which visual tokens are retained; the block consumes

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libskipffn.so")
 FLAG_DW_FP32 = 0x1
 FLAG_DW_ACCUMULATE = 0x2
 FLAG_NO_RESIDUAL = 0x4
+FLAG_BALANCED_SPLIT = 0x8
 
 OK, EINVAL, ESHAPE, EWORKSPACE, EHIP, EUNSUPPORTED = range(6)
 

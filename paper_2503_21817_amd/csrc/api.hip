@@ -39,19 +39,37 @@ hipError_t ensure_gemm_init() {
 
 constexpr int kMaxSplits = 8;
 
-// Split-K factor for a GEMM with `tiles` output tiles and `ktiles` K slabs on 256
-// CUs (one workgroup per CU).  Cost in units of one K slab of one tile: every
-// round of 256 workgroups costs its slab count plus a fixed prologue/epilogue,
-// partial tiles cost a write now and a read in the reducing kernel.
-int choose_splits(int tiles, int ktiles) {
-    int best = 1;
+// How the K range of a GEMM with tiles_m x tiles_n output tiles and `ktiles` K slabs is cut
+// on 256 CUs (one workgroup per CU).  Costs are in units of one K slab of one tile: every
+// round of 256 workgroups costs its slab count plus a fixed prologue/epilogue, partial tiles
+// cost a write now and a read in the reducing kernel.
+//   splits == 1, sk_nbg == 0 : one workgroup per tile, epilogue fused
+//   splits  > 1, sk_nbg == 0 : plain split-K into `splits` fp32 slabs
+//   sk_nbg  > 0              : balanced split (gemm_bf16_streamk_kernel), sk_nbg workgroups per
+//                              n-tile group; chosen only while a group's tiles fit its workgroups
+struct KPartition { int splits; int sk_nbg; };
+KPartition choose_k_partition(int tiles_m, int tiles_n, int ktiles, bool force_balanced) {
+    const int tiles = tiles_m * tiles_n;
+    KPartition best{1, 0};
     double best_cost = 1e30;
     for (int s = 1; s <= kMaxSplits; ++s) {
         int per = (ktiles + s - 1) / s;
         if (s > 1 && per < 8) break;
         int rounds = (tiles * s + 255) / 256;
         double cost = rounds * (per + 8.0 + (s > 1 ? 8.0 : 0.0)) + (s > 1 ? 0.04 * s * tiles : 0.0);
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{s, 0}; }
+    }
+    const int nbg = tiles_n > 0 ? 256 / tiles_n : 0;
+    if (nbg >= 1 && tiles_m <= nbg && tiles > 0) {
+        const StreamKPlan p = streamk_plan(tiles_m, ktiles, nbg);
+        if (force_balanced) return KPartition{1, nbg};
+        if (p.q >= 8) {
+            double slabs = 0.0;
+            for (int i = 0; i < tiles_m; ++i) slabs += streamk_count(p, i);
+            // a remainder piece may run two short segments: charge a second prologue/epilogue
+            double cost = p.q + 16.0 + (p.nr > 0 ? 16.0 : 0.0) + 0.04 * slabs * tiles_n;
+            if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{1, nbg}; }
+        }
     }
     return best;
 }
@@ -320,23 +338,26 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         a.A0 = H; a.lda = (int)I; a.a_bytes = (uint32_t)(Rb * I * 2);
         a.B0 = static_cast<const bf16_t*>(w_down); a.ldb = (int)I; a.b_bytes = (uint32_t)(C * I * 2);
         a.pairs = 1;
-        const int tiles = (int)((Rb + BM - 1) / BM) * (int)((C + BN - 1) / BN);
+        const int tiles_m = (int)((Rb + BM - 1) / BM), tiles_n = (int)((C + BN - 1) / BN);
         const int ktiles = (int)((I + BK - 1) / BK);
-        a.splits = choose_splits(tiles, ktiles);
+        const KPartition kp = choose_k_partition(tiles_m, tiles_n, ktiles, (flags & SKIPFFN_FLAG_BALANCED_SPLIT) != 0);
+        a.splits = kp.splits;
         a.idx = idx; a.ldo = (int)C;
         a.no_residual = (flags & SKIPFFN_FLAG_NO_RESIDUAL) ? 1 : 0;
         profile_mark_begin(KC_GEMM_DOWN, s);
-        if (a.splits == 1) {
+        if (kp.splits == 1 && kp.sk_nbg == 0) {
             a.out0 = out; a.e0 = static_cast<const bf16_t*>(hidden);
             e = launch_gemm(true, true, EPI_RESID_SCATTER, a, s);
             profile_mark_end(KC_GEMM_DOWN, s);
             if (e != hipSuccess) return hip_fail(e);
         } else {
             a.partial = partial;
-            e = launch_gemm(true, true, EPI_PARTIAL, a, s);
+            e = kp.sk_nbg > 0 ? launch_gemm_streamk(true, true, a, kp.sk_nbg, s)
+                              : launch_gemm(true, true, EPI_PARTIAL, a, s);
             profile_mark_end(KC_GEMM_DOWN, s);
             if (e != hipSuccess) return hip_fail(e);
-            e = launch_resid_scatter(partial, a.splits, (int)Rb, r_dev, (int)C, idx,
+            const PartialLayout pl{kp.splits, kp.sk_nbg, ktiles};
+            e = launch_resid_scatter(partial, pl, (int)Rb, r_dev, (int)C, idx,
                                      static_cast<const bf16_t*>(hidden), static_cast<bf16_t*>(out),
                                      a.no_residual, s);
             if (e != hipSuccess) return hip_fail(e);
@@ -449,7 +470,7 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     }
     // dxn = dG * W_gate + dU * W_up  (K runs over both pairs), fp32 split-K slabs.  (Sharing a
     // grid with the dW GEMMs above was measured slower: both are already well balanced.)
-    int splits;
+    PartialLayout pl{1, 0, 0};
     {
         GemmArgs a{};
         a.M = (int)Rb; a.N = (int)C; a.K = (int)I; a.m_dev = r_dev;
@@ -457,17 +478,20 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         a.B0 = static_cast<const bf16_t*>(w_gate); a.B1 = static_cast<const bf16_t*>(w_up);
         a.ldb = (int)C; a.b_bytes = (uint32_t)(I * C * 2);
         a.pairs = 2;
-        const int tiles = (int)((Rb + BM - 1) / BM) * (int)((C + BN - 1) / BN);
+        const int tiles_m = (int)((Rb + BM - 1) / BM), tiles_n = (int)((C + BN - 1) / BN);
         const int ktiles = 2 * (int)((I + BK - 1) / BK);
-        a.splits = splits = choose_splits(tiles, ktiles);
+        const KPartition kp = choose_k_partition(tiles_m, tiles_n, ktiles, (flags & SKIPFFN_FLAG_BALANCED_SPLIT) != 0);
+        a.splits = kp.splits;
+        pl = PartialLayout{kp.splits, kp.sk_nbg, ktiles};
         a.partial = partial;
         profile_mark_begin(KC_GEMM_DXN, s);
-        e = launch_gemm(true, false, EPI_PARTIAL, a, s);
+        e = kp.sk_nbg > 0 ? launch_gemm_streamk(true, false, a, kp.sk_nbg, s)
+                          : launch_gemm(true, false, EPI_PARTIAL, a, s);
         profile_mark_end(KC_GEMM_DXN, s);
         if (e != hipSuccess) return hip_fail(e);
     }
     // RMSNorm backward + residual gradient, scattered to the retained rows
-    e = launch_rmsnorm_bwd_scatter(partial, splits, (int)Rb, r_dev, (int)C, xrows, rstd,
+    e = launch_rmsnorm_bwd_scatter(partial, pl, (int)Rb, r_dev, (int)C, xrows, rstd,
                                    static_cast<const bf16_t*>(rms_gain), dY, idx,
                                    static_cast<bf16_t*>(grad_hidden), s);
     if (e != hipSuccess) return hip_fail(e);

@@ -29,6 +29,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "streamk.hpp"
 
 namespace skipffn {
 
@@ -163,9 +164,12 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
     tm = p * PANEL_M + (in_panel - tn * pm);
 }
 
-// One workgroup's share of a GEMM: `block` of `nblocks` in the launch order of this problem.
+// One output tile (tm, tn) over the K slabs [kt_begin, kt_end) of the concatenated pairs;
+// z selects the fp32 slab an EPI_PARTIAL result goes to.
 template <bool A_KC, bool B_KC, int EPI>
-__device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const int nblocks) {
+__device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const int tn, const int z,
+                                          const int kt_begin, const int kt_end, const int Meff,
+                                          const int Keff) {
     extern __shared__ __align__(16) char smem[];
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -173,29 +177,9 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     const int wm = wave >> 2;      // 0..1
     const int wn = wave & 3;       // 0..3
 
-    int tm, tn, z;
-    tile_of_block(block, nblocks, P.tiles_m, P.tiles_n, tm, tn, z);
-    // batched launch (two problems in one grid, used for dW_gate / dW_up): the upper half of
-    // the z range is problem 1
-    const bool second = P.batch == 2 && z >= P.splits;
-    if (second) {
-        z -= P.splits;
-        if (EPI == EPI_STORE_T) P.B0 = P.B1; else P.A0 = P.A1;
-        P.out0 = P.out1;
-    }
-
-    const int Meff = effective_rows(P.M, P.m_dev);
-    const int Keff = effective_rows(P.K, P.k_dev);
     const int m0 = tm * BM;
     const int n0 = (EPI == EPI_SWIGLU) ? tn * (BN / 2) : tn * BN;
-    if (m0 >= Meff) return;    // whole block leaves together: no barrier was reached yet
-
     const int ktiles_pair = (Keff + BK - 1) / BK;
-    const int ktotal = ktiles_pair * P.pairs;
-    const int per_split = (ktotal + P.splits - 1) / P.splits;
-    const int kt_begin = z * per_split;
-    int kt_end = kt_begin + per_split;
-    if (kt_end > ktotal) kt_end = ktotal;
     const int nk = kt_end > kt_begin ? kt_end - kt_begin : 0;
 
     __amdgpu_buffer_rsrc_t rA0 = make_rsrc(P.A0, P.a_bytes);
@@ -618,6 +602,31 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     }
 }
 
+// One workgroup's share of a plain (optionally split-K, optionally batched) GEMM: `block` of
+// `nblocks` in the launch order of this problem.
+template <bool A_KC, bool B_KC, int EPI>
+__device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const int nblocks) {
+    int tm, tn, z;
+    tile_of_block(block, nblocks, P.tiles_m, P.tiles_n, tm, tn, z);
+    // batched launch (two problems in one grid, used for dW_gate / dW_up): the upper half of
+    // the z range is problem 1
+    const bool second = P.batch == 2 && z >= P.splits;
+    if (second) {
+        z -= P.splits;
+        if (EPI == EPI_STORE_T) P.B0 = P.B1; else P.A0 = P.A1;
+        P.out0 = P.out1;
+    }
+    const int Meff = effective_rows(P.M, P.m_dev);
+    const int Keff = effective_rows(P.K, P.k_dev);
+    if (tm * BM >= Meff) return;    // whole block leaves together: no barrier was reached yet
+    const int ktotal = ((Keff + BK - 1) / BK) * P.pairs;
+    const int per_split = (ktotal + P.splits - 1) / P.splits;
+    const int kt_begin = z * per_split;
+    int kt_end = kt_begin + per_split;
+    if (kt_end > ktotal) kt_end = ktotal;
+    gemm_tile<A_KC, B_KC, EPI>(P, tm, tn, z, kt_begin, kt_end, Meff, Keff);
+}
+
 template <bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
     gemm_block<A_KC, B_KC, EPI>(P, (int)blockIdx.x, (int)gridDim.x);
@@ -636,6 +645,32 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_dual_kernel(GemmArgs P
         if (b < real0) gemm_block<A0_KC, B0_KC, EPI0>(P0, b, real0);
     } else {
         gemm_block<A1_KC, B1_KC, EPI1>(P1, b - nblocks0, (int)gridDim.x - nblocks0);
+    }
+}
+
+// ---- balanced split-K for GEMMs that leave through fp32 partial slabs (see streamk.hpp) ------
+// grid = tiles_n * nbg workgroups (P.splits carries nbg); EPI_PARTIAL only
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_streamk_kernel(GemmArgs P) {
+    const int nbg = P.splits;
+    const int nb = (int)gridDim.x;
+    int b = (int)blockIdx.x;
+    // workgroups are dealt round-robin to the 8 XCDs: give each XCD whole groups
+    if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
+    const int tn = b / nbg, j = b - tn * nbg;
+    const int Meff = effective_rows(P.M, P.m_dev);
+    const int Keff = effective_rows(P.K, P.k_dev);
+    const int g = (Meff + BM - 1) / BM;
+    const int kt = ((Keff + BK - 1) / BK) * P.pairs;
+    if (g == 0 || kt == 0) return;
+    const StreamKPlan p = streamk_plan(g, kt, nbg);
+    StreamKIter it = streamk_begin(p, j);
+    StreamKSeg sg;
+    bool first = true;
+    while (streamk_next(p, it, sg)) {      // uniform over the workgroup
+        if (!first) lds_barrier();          // the staging buffers of the previous epilogue are free again
+        first = false;
+        gemm_tile<A_KC, B_KC, EPI_PARTIAL>(P, sg.i, tn, sg.slot, sg.kb, sg.ke, Meff, Keff);
     }
 }
 

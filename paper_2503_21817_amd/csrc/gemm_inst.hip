@@ -21,6 +21,12 @@ hipError_t gemm_init() {
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, false, EPI_STORE>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_streamk_kernel<true, true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_streamk_kernel<true, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e != hipSuccess) return e;
     return hipSuccess;
 }
 
@@ -49,6 +55,21 @@ hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s
     if (real0 <= 0 || n1 <= 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL((gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, false, EPI_STORE>),
                        dim3((unsigned)(n0 + n1)), dim3(GEMM_THREADS), GEMM_LDS_BYTES, s, a0, a1, n0, real0);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_streamk(bool a_kc, bool b_kc, GemmArgs& a, int nbg, hipStream_t s) {
+    finish_args(EPI_PARTIAL, a);
+    if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
+    if (nbg < 1 || !a_kc || a.batch != 1) return hipErrorInvalidValue;
+    a.splits = nbg;
+    const unsigned blocks = (unsigned)(a.tiles_n * nbg);
+    if (b_kc)
+        hipLaunchKernelGGL((gemm_bf16_streamk_kernel<true, true>), dim3(blocks), dim3(GEMM_THREADS),
+                           GEMM_LDS_BYTES, s, a);
+    else
+        hipLaunchKernelGGL((gemm_bf16_streamk_kernel<true, false>), dim3(blocks), dim3(GEMM_THREADS),
+                           GEMM_LDS_BYTES, s, a);
     return hipGetLastError();
 }
 

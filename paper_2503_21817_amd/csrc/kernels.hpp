@@ -40,8 +40,12 @@ hipError_t launch_compact(const uint8_t* mask, int64_t T, int32_t* idx, int32_t*
 hipError_t launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* idx, int R,
                                  const int32_t* r_dev, int C, float eps, const bf16_t* gain,
                                  bf16_t* xrows, bf16_t* xn, float* rstd, hipStream_t s);
+// How many fp32 partial slabs a reducing kernel adds per output element: `splits` for a plain
+// split-K GEMM (sk_nbg == 0), else the per-tile count of the balanced split (streamk_count)
+// with sk_nbg workgroups per n-tile group and sk_kt K slabs per tile.
+struct PartialLayout { int splits; int sk_nbg; int sk_kt; };
 // out[idx[r]] = bf16(res[idx[r]] + sum_z partial[z][r])
-hipError_t launch_resid_scatter(const float* partial, int splits, int R, const int32_t* r_dev,
+hipError_t launch_resid_scatter(const float* partial, PartialLayout pl, int R, const int32_t* r_dev,
                                 int C, const int32_t* idx, const bf16_t* res, bf16_t* out,
                                 int no_residual, hipStream_t s);
 // dst[r] = src[idx[r]]  (rows of row_bytes, multiple of 16)
@@ -56,7 +60,7 @@ hipError_t launch_gather_transpose(const bf16_t* src, int C, const int32_t* idx,
 hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row_bytes,
                               const int32_t* idx, int R, const int32_t* r_dev, hipStream_t s);
 // dX[idx[r]] = bf16(dY[r] + rmsnorm_bwd(sum_z dxn_partial[z][r], x[r], rstd[r], gain))
-hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int R,
+hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl, int R,
                                       const int32_t* r_dev, int C, const bf16_t* xrows,
                                       const float* rstd, const bf16_t* gain, const bf16_t* dY,
                                       const int32_t* idx, bf16_t* dX, hipStream_t s);
@@ -71,5 +75,7 @@ enum DualKind : int {
     DUAL_DH_DWDOWN = 0    // <KC,MNC,SWIGLU_BWD> (dH -> dG, dU)  +  <KC,MNC,STORE> (dW_down = dY^T * H)
 };
 hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s);
+// balanced split-K GEMM into fp32 partial slabs (EPI_PARTIAL): nbg workgroups per n-tile group
+hipError_t launch_gemm_streamk(bool a_kc, bool b_kc, GemmArgs& args, int nbg, hipStream_t s);
 
 }  // namespace skipffn

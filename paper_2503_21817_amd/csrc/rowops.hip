@@ -122,8 +122,16 @@ hipError_t launch_gather_rmsnorm(const bf16_t* hidden, const int32_t* idx, int R
 // ---- split-K reduce + residual + scatter ----------------------------------------------
 // out[idx[r]][c] = bf16( res[idx[r]][c] + sum_z partial[z][r][c] ), summed in z order.
 // One thread per 16-byte chunk of the output.
+// number of partial slabs to add for row r, column col
+__device__ __forceinline__ int partial_count(const PartialLayout& pl, int R, int r, int col) {
+    if (pl.sk_nbg == 0) return pl.splits;
+    const StreamKPlan p = streamk_plan((R + BM - 1) / BM, pl.sk_kt, pl.sk_nbg);
+    (void)col;                       // the count depends on the m-tile only
+    return streamk_count(p, r / BM);
+}
+
 __global__ __launch_bounds__(ROW_THREADS) void resid_scatter_kernel(
-    const float* __restrict__ partial, int splits, int Rbound, const int32_t* __restrict__ r_dev,
+    const float* __restrict__ partial, PartialLayout pl, int Rbound, const int32_t* __restrict__ r_dev,
     int C, const int32_t* __restrict__ idx, const bf16_t* res, bf16_t* out, int no_residual) {
     const int R = effective_rows(Rbound, r_dev);
     const int chunks = C >> 3;
@@ -136,6 +144,7 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_scatter_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
     const float* p = partial + (int64_t)r * C + c * 8;
+    const int splits = partial_count(pl, R, r, c * 8);
     for (int z = 0; z < splits; ++z) {
         f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride);
         f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + 4);
@@ -154,14 +163,14 @@ __global__ __launch_bounds__(ROW_THREADS) void resid_scatter_kernel(
     *reinterpret_cast<u32x4*>(out + orow + c * 8) = pack8(acc);
 }
 
-hipError_t launch_resid_scatter(const float* partial, int splits, int R, const int32_t* r_dev,
+hipError_t launch_resid_scatter(const float* partial, PartialLayout pl, int R, const int32_t* r_dev,
                                 int C, const int32_t* idx, const bf16_t* res, bf16_t* out,
                                 int no_residual, hipStream_t s) {
     if (R <= 0) return hipSuccess;
     const int64_t total = (int64_t)R * (C >> 3);
     dim3 grid((unsigned)((total + ROW_THREADS - 1) / ROW_THREADS)), block(ROW_THREADS);
     profile_mark_begin(KC_RESID_SCATTER, s);
-    hipLaunchKernelGGL(resid_scatter_kernel, grid, block, 0, s, partial, splits, R, r_dev, C, idx,
+    hipLaunchKernelGGL(resid_scatter_kernel, grid, block, 0, s, partial, pl, R, r_dev, C, idx,
                        res, out, no_residual);
     profile_mark_end(KC_RESID_SCATTER, s);
     return hipGetLastError();
@@ -290,7 +299,7 @@ hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row
 // dG*W_gate + dU*W_up GEMM), added here in z order.
 template <bool IN_REGS>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
-    const float* __restrict__ part, int splits, int Rbound, const int32_t* __restrict__ r_dev,
+    const float* __restrict__ part, PartialLayout pl, int Rbound, const int32_t* __restrict__ r_dev,
     int C, const bf16_t* __restrict__ xrows, const float* __restrict__ rstd_in,
     const bf16_t* __restrict__ gain, const bf16_t* __restrict__ dY,
     const int32_t* __restrict__ idx, bf16_t* dX) {
@@ -303,6 +312,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     const float rstd = rstd_in[r];
     const int64_t zstride = (int64_t)Rbound * C;
     const float* p = part + (int64_t)r * C;
+    const int splits = partial_count(pl, R, r, 0);
     const u32x4* xs = reinterpret_cast<const u32x4*>(xrows + (int64_t)r * C);
     const u32x4* gs = reinterpret_cast<const u32x4*>(gain);
 
@@ -377,7 +387,7 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     }
 }
 
-hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int R,
+hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl, int R,
                                       const int32_t* r_dev, int C, const bf16_t* xrows,
                                       const float* rstd, const bf16_t* gain, const bf16_t* dY,
                                       const int32_t* idx, bf16_t* dX, hipStream_t s) {
@@ -385,10 +395,10 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, int splits, int 
     dim3 grid(R), block(ROW_THREADS);
     profile_mark_begin(KC_RMSNORM_BWD, s);
     if (C <= 4096)
-        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<true>, grid, block, 0, s, dxn_partial, splits,
+        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<true>, grid, block, 0, s, dxn_partial, pl,
                            R, r_dev, C, xrows, rstd, gain, dY, idx, dX);
     else
-        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<false>, grid, block, 0, s, dxn_partial, splits,
+        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<false>, grid, block, 0, s, dxn_partial, pl,
                            R, r_dev, C, xrows, rstd, gain, dY, idx, dX);
     profile_mark_end(KC_RMSNORM_BWD, s);
     return hipGetLastError();

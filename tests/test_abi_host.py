@@ -101,7 +101,7 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert bwd(saved=None) == B.EINVAL
     assert bwd(dwg=None) == B.EINVAL
     assert bwd(dwd=ODD) == B.EINVAL
-    assert bwd(flags=0x8) == B.EUNSUPPORTED
+    assert bwd(flags=0x10) == B.EUNSUPPORTED
     assert bwd(ws_bytes=0) == B.EWORKSPACE
 
 

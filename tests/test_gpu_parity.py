@@ -268,3 +268,42 @@ def test_random_shapes_forward_backward(seed):
         assert rel_l2(O.bf16_bits_to_f64(gb[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
         for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
             assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, (k, r_host)
+
+
+BALANCED = [
+    # (workload, what it exercises)
+    W.small(C=512, I=1368, visual=(300, 411), text=(20, 35), keep=(130, 212), seed=21,
+            name="bal-2groups-2tiles"),           # 2 m-tiles, K tail, aligned chunks + remainder pieces
+    W.small(C=264, I=520, visual=(700,), text=(9,), keep=(600,), seed=22,
+            name="bal-3tiles-short-k"),           # ragged C, few K slabs: q from the slab budget
+    W.small(C=1024, I=2048, visual=(64,), text=(1,), keep=(0,), seed=23, name="bal-one-row"),
+    W.small(C=256, I=9000, visual=(900, 600), text=(30, 12), keep=(450, 333), seed=24,
+            name="bal-long-k-4tiles"),            # long K, remainder pieces spanning tiles
+]
+
+
+@pytest.mark.parametrize("w", BALANCED, ids=lambda w: w.name)
+@pytest.mark.parametrize("r_host", [True, False], ids=["R-host", "R-device"])
+def test_balanced_split_forward_backward(w, r_host):
+    """The balanced K split of the down and dXn GEMMs (forced by flag: the cost model would
+    not pick it at these sizes) against the oracle, with R known on the host and R read on
+    the device (the plan is then recomputed in the kernels from the device-side count)."""
+    p = Problem(w, unit_gain=False)
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    idx = fo["idx"]
+    sk = p.mask != 0
+    out, bufs = gpu_forward(p, R_host=r_host, flags=B.FLAG_BALANCED_SPLIT)
+    got = bits_of(out)
+    assert np.array_equal(got[sk], p.hidden[sk])
+    assert rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx])) < REL_L2_TOL
+    gh, dw = gpu_backward(p, bufs, R_host=r_host, flags=B.FLAG_BALANCED_SPLIT)
+    gb = bits_of(gh)
+    assert np.array_equal(gb[sk], p.grad[sk])
+    assert rel_l2(O.bf16_bits_to_f64(gb[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
+    # the split only changes the order of fp32 additions: results agree with the default path
+    out2, bufs2 = gpu_forward(p, R_host=r_host)
+    gh2, _ = gpu_backward(p, bufs2, R_host=r_host)
+    a, b = f64_of(out)[idx], f64_of(out2)[idx]
+    assert rel_l2(a, b) < 1e-2
+    assert rel_l2(f64_of(gh)[idx], f64_of(gh2)[idx]) < 1e-2
