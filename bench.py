@@ -45,10 +45,12 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
-                         "T = 2^16 .. 2^26.  The JSON line then carries a 'sweep' array")
+                         "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
+                         "(32 layers x key/value x 8 heads x 128) for the token mixes of configurations "
+                         "2, 3 and 5.  The JSON line then carries a 'sweep' array")
     ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
@@ -215,6 +217,45 @@ def compact_sweep(torch, B, args):
             "config": {"workload": "mask compaction, 25 % retained, T = 2^13 .. 2^26"}, "sweep": rows}
 
 
+def kv_sweep(torch, B, W, args):
+    """Skip KV-cache (Section 4.3) on a packed cache [layers, 2, kv heads, T, head dim] of the
+    backbone (32 x 2 x 8 x T x 128, bf16): algorithmic bytes = read + write of the retained
+    rows, 2 * slabs * R * 256 B, against HIP-event time."""
+    rows = []
+    L, H, D = 32, 8, 128
+    for cfg in (2, 3, 5):
+        w = W.config(cfg)
+        T, R = w.T, w.R
+        mask = torch.from_numpy(W.make_mask(w)).cuda()
+        idx = torch.empty(T, dtype=torch.int32, device="cuda")
+        nret = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(max(B.skipffn_compact_workspace_bytes(T), 16), dtype=torch.uint8, device="cuda")
+        B.skipffn_compact(mask, idx, nret, None, ws)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(500 + cfg)
+        src = torch.randn((L, 2, H, T, D), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        dst = torch.empty((L, 2, H, R, D), dtype=torch.bfloat16, device="cuda")
+        for _ in range(args.warmup):
+            B.skipffn_kv_compact(src, dst, idx, R)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.skipffn_kv_compact(src, dst, idx, R)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        assert torch.equal(dst[3, 1, 5], src[3, 1, 5][idx[:R].long()])
+        nbytes = 2 * L * 2 * H * R * D * 2
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        rows.append({"workload": w.name, "T": T, "R": R, "cache_MB": round(src.numel() * 2 / 1e6, 1),
+                     "us": round(ms * 1e3, 1), "gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)})
+        del src, dst
+    return {"metric": "skip KV-cache compaction bandwidth", "unit": "GB/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "dtype": "bf16 (bit copy)", "data": "synthetic",
+            "config": {"workload": "LLaMA-3-8B cache, packed batch, token mixes of configurations 2, 3, 5"},
+            "sweep": rows}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -236,6 +277,9 @@ def main():
     bwd = args.passes == "fwd+bwd"
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "kv":
+        print(json.dumps(kv_sweep(torch, B, W, args)))
         return
     if args.sweep == "retention":
         print(json.dumps(retention_sweep(torch, B, W, w, bwd, args)))

@@ -139,6 +139,19 @@ int skipffn_gather_rows(const void* src, void* dst, int64_t T, int64_t row_bytes
                         const int32_t* idx, int64_t R, const int32_t* num_retained,
                         void* stream);
 
+/* Whole-cache form of the same set difference: a cache holds n_slabs slabs (one per layer,
+ * key/value, batch entry and head - whatever precedes the token axis in the caller's
+ * layout), each [T, row_bytes]; slab s starts at src + s * src_slab_bytes.  For every slab
+ *     dst[s][r, :] = src[s][idx[r], :]   for r < R,
+ * slab s of dst starting at dst + s * dst_slab_bytes (dst_slab_bytes >= R_max * row_bytes,
+ * so the compacted cache may keep the prefill capacity or be packed).  One launch for the
+ * whole cache.  row_bytes, src_slab_bytes, dst_slab_bytes are multiples of 16; src and dst
+ * must not overlap (compacting in place would race: row r is a source for an earlier
+ * destination).  n_slabs == 0 or R == 0: nothing is done. */
+int skipffn_kv_compact(const void* src, void* dst, int64_t n_slabs, int64_t T, int64_t row_bytes,
+                       int64_t src_slab_bytes, int64_t dst_slab_bytes,
+                       const int32_t* idx, int64_t R, const int32_t* num_retained, void* stream);
+
 /* ---- layout of `saved`, for tests that compare stage by stage -------------
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];

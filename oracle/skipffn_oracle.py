@@ -328,3 +328,15 @@ def kv_skip_cache(cache_bits, skip):
     the rows of retained tokens, in token order - K_cache minus K_skip."""
     idx, _, _ = compact(skip)
     return np.ascontiguousarray(np.asarray(cache_bits)[idx])
+
+
+def kv_skip_cache_all(cache_bits, skip):
+    """cache_bits uint16 [..., T, D] (every leading index is one slab: layer, key/value,
+    head ...): the same set difference applied to every slab, one after the other."""
+    c = np.asarray(cache_bits)
+    lead = c.shape[:-2]
+    flat = c.reshape((-1,) + c.shape[-2:])
+    out = [kv_skip_cache(flat[s], skip) for s in range(flat.shape[0])]
+    R = out[0].shape[0] if out else int((np.asarray(skip) == 0).sum())
+    return np.stack(out).reshape(lead + (R, c.shape[-1])) if out else np.zeros(lead + (R, c.shape[-1]), c.dtype)
+

@@ -42,6 +42,8 @@ _SIGNATURES = {
                                  c_size_t, c_uint32, c_void_p]),
     "skipffn_gather_rows": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64,
                                     c_void_p, c_void_p]),
+    "skipffn_kv_compact": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int64, c_int64,
+                                   c_void_p, c_int64, c_void_p, c_void_p]),
     "skipffn_saved_layout": (c_int, [c_int64, c_int64, c_int64, POINTER(c_size_t)]),
     "skipffn_status_string": (c_char_p, [c_int]),
     "skipffn_last_hip_error": (c_int, []),
@@ -168,6 +170,18 @@ def skipffn_gather_rows(src, dst, idx, R, *, num_retained=None):
     Rv, nr = _rargs(R, num_retained)
     _check(lib().skipffn_gather_rows(_ptr(src), _ptr(dst), T, row_bytes, _ptr(idx), Rv, nr,
                                      _stream()), "skipffn_gather_rows")
+
+
+def skipffn_kv_compact(src, dst, idx, R, *, num_retained=None):
+    """src [..., T, D] -> dst [..., R_cap, D] (same leading dims, any R_cap >= R): every
+    leading index is one slab.  Both tensors are contiguous."""
+    T, D = src.shape[-2], src.shape[-1]
+    n_slabs = src.numel() // max(T * D, 1)
+    row_bytes = D * src.element_size()
+    Rv, nr = _rargs(R, num_retained)
+    _check(lib().skipffn_kv_compact(_ptr(src), _ptr(dst), n_slabs, T, row_bytes, T * row_bytes,
+                                    dst.shape[-2] * row_bytes, _ptr(idx), Rv, nr, _stream()),
+           "skipffn_kv_compact")
 
 
 def skipffn_version() -> int:

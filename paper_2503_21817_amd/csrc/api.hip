@@ -141,7 +141,7 @@ const char* kernel_class_name(int kc) {
     static const char* names[KC_COUNT] = {
         "compact", "gather_rmsnorm", "gemm_gate_up_swiglu", "gemm_down", "resid_scatter",
         "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd+dw_down", "gemm_dw_gate_up",
-        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero"};
+        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact"};
     return (kc >= 0 && kc < KC_COUNT) ? names[kc] : "?";
 }
 
@@ -510,6 +510,28 @@ int skipffn_gather_rows(const void* src, void* dst, int64_t T, int64_t row_bytes
     if (T > 0x7fffffff) return SKIPFFN_ESHAPE;
     hipError_t e = launch_gather_rows(src, dst, row_bytes, idx, (int)Rb, R < 0 ? num_retained : nullptr,
                                       (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+int skipffn_kv_compact(const void* src, void* dst, int64_t n_slabs, int64_t T, int64_t row_bytes,
+                       int64_t src_slab_bytes, int64_t dst_slab_bytes, const int32_t* idx,
+                       int64_t R, const int32_t* num_retained, void* stream) {
+    if (n_slabs < 0 || T < 0 || row_bytes < 0 || R < -1 || R > T) return SKIPFFN_EINVAL;
+    if (R == -1 && num_retained == nullptr) return SKIPFFN_EINVAL;
+    if ((row_bytes & 15) || (src_slab_bytes & 15) || (dst_slab_bytes & 15)) return SKIPFFN_ESHAPE;
+    const int64_t Rb = R < 0 ? T : R;
+    if (Rb == 0 || row_bytes == 0 || n_slabs == 0) return SKIPFFN_OK;
+    if (bad_ptr(src) || bad_ptr(dst) || idx == nullptr) return SKIPFFN_EINVAL;
+    if (T > 0x7fffffff || row_bytes > ((int64_t)1 << 24)) return SKIPFFN_ESHAPE;
+    if (Rb * (row_bytes / 16) >= ((int64_t)1 << 31) * (int64_t)256) return SKIPFFN_ESHAPE;
+    if (src_slab_bytes < T * row_bytes || dst_slab_bytes < Rb * row_bytes) return SKIPFFN_EINVAL;
+    // the two caches may not overlap
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(src), b0 = reinterpret_cast<uintptr_t>(dst);
+    const uintptr_t a1 = a0 + (uintptr_t)((n_slabs - 1) * src_slab_bytes + T * row_bytes);
+    const uintptr_t b1 = b0 + (uintptr_t)((n_slabs - 1) * dst_slab_bytes + Rb * row_bytes);
+    if (a0 < b1 && b0 < a1) return SKIPFFN_EINVAL;
+    hipError_t e = launch_kv_compact(src, dst, n_slabs, row_bytes, src_slab_bytes, dst_slab_bytes, idx,
+                                     (int)Rb, R < 0 ? num_retained : nullptr, (hipStream_t)stream);
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 

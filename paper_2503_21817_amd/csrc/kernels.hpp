@@ -24,6 +24,7 @@ enum KernelClass : int {
     KC_GEMM_DXN,
     KC_RMSNORM_BWD,
     KC_FILL,
+    KC_KV_COMPACT,
     KC_COUNT
 };
 const char* kernel_class_name(int kc);
@@ -51,6 +52,10 @@ hipError_t launch_resid_scatter(const float* partial, PartialLayout pl, int R, c
 // dst[r] = src[idx[r]]  (rows of row_bytes, multiple of 16)
 hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, const int32_t* idx,
                               int R, const int32_t* r_dev, hipStream_t s);
+// dst[s][r] = src[s][idx[r]] for n_slabs slabs (slab strides in bytes, multiples of 16)
+hipError_t launch_kv_compact(const void* src, void* dst, int64_t n_slabs, int64_t row_bytes,
+                             int64_t src_slab_bytes, int64_t dst_slab_bytes, const int32_t* idx,
+                             int R, const int32_t* r_dev, hipStream_t s);
 // dst[r] = src[idx ? idx[r] : r] (dst optional) and the transposed copy dstT[c][r], leading
 // dimension ldT (multiple of 8, >= R bound), columns r >= R zero
 hipError_t launch_gather_transpose(const bf16_t* src, int C, const int32_t* idx, int R,

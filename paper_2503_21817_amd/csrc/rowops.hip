@@ -201,6 +201,42 @@ hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, con
     return hipGetLastError();
 }
 
+// ---- skip KV-cache over a whole cache (Section 4.3) --------------------------------------------
+// One thread per 16-byte chunk of the compacted cache; blockIdx.y walks the slabs.  Cache rows
+// are short (one head of one token: 256 bytes for d = 128), so a wavefront per row would
+// leave three quarters of its lanes idle.
+__global__ __launch_bounds__(ROW_THREADS) void kv_compact_kernel(
+    const char* __restrict__ src, char* __restrict__ dst, int64_t n_slabs, int row_chunks,
+    int64_t src_slab_bytes, int64_t dst_slab_bytes, const int32_t* __restrict__ idx, int Rbound,
+    const int32_t* __restrict__ r_dev) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int64_t g = (int64_t)blockIdx.x * ROW_THREADS + threadIdx.x;
+    const int r = (int)(g / row_chunks), c = (int)(g - (int64_t)r * row_chunks);
+    if (r >= R) return;
+    const int64_t so = (int64_t)idx[r] * row_chunks + c, d_o = (int64_t)r * row_chunks + c;
+    for (int64_t sl = blockIdx.y; sl < n_slabs; sl += gridDim.y) {
+        const u32x4* s = reinterpret_cast<const u32x4*>(src + sl * src_slab_bytes);
+        u32x4* d = reinterpret_cast<u32x4*>(dst + sl * dst_slab_bytes);
+        d[d_o] = s[so];
+    }
+}
+
+hipError_t launch_kv_compact(const void* src, void* dst, int64_t n_slabs, int64_t row_bytes,
+                             int64_t src_slab_bytes, int64_t dst_slab_bytes, const int32_t* idx,
+                             int R, const int32_t* r_dev, hipStream_t s) {
+    if (R <= 0 || row_bytes <= 0 || n_slabs <= 0) return hipSuccess;
+    const int row_chunks = (int)(row_bytes / 16);
+    const int64_t per_slab = (int64_t)R * row_chunks;
+    dim3 grid((unsigned)((per_slab + ROW_THREADS - 1) / ROW_THREADS),
+              (unsigned)(n_slabs < 65535 ? n_slabs : 65535)), block(ROW_THREADS);
+    profile_mark_begin(KC_KV_COMPACT, s);
+    hipLaunchKernelGGL(kv_compact_kernel, grid, block, 0, s, static_cast<const char*>(src),
+                       static_cast<char*>(dst), n_slabs, row_chunks, src_slab_bytes, dst_slab_bytes,
+                       idx, R, r_dev);
+    profile_mark_end(KC_KV_COMPACT, s);
+    return hipGetLastError();
+}
+
 // ---- row gather with a transposed copy ------------------------------------------------------
 // dst[r][:] = src[row(r)][:] (optional) and dstT[c][r] = src[row(r)][c], where row(r) = idx[r]
 // (or r when idx is null).  dstT has leading dimension ldT (a multiple of 8 >= the row

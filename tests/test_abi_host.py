@@ -115,6 +115,20 @@ def test_compact_and_gather_reject_bad_arguments_on_the_host():
     assert lib.skipffn_gather_rows(FAKE, FAKE, 10, 32, FAKE, 11, None, None) == B.EINVAL
     assert lib.skipffn_gather_rows(None, FAKE, 10, 32, FAKE, 3, None, None) == B.EINVAL
     assert lib.skipffn_gather_rows(FAKE, FAKE, 10, 32, FAKE, 0, None, None) == B.OK
+    # whole-cache form: src, dst, n_slabs, T, row_bytes, slab strides, idx, R, num_retained, stream;
+    # only calls that are rejected (or are no-ops) before anything is enqueued
+    kv = lib.skipffn_kv_compact
+    FAR = ctypes.c_void_p(0x7000_0000_0000)
+    assert kv(FAKE, FAR, 4, 10, 24, 240, 240, FAKE, 3, None, None) == B.ESHAPE      # row not 16-byte
+    assert kv(FAKE, FAR, 4, 10, 32, 328, 320, FAKE, 3, None, None) == B.ESHAPE      # stride not 16-byte
+    assert kv(FAKE, FAR, 4, 10, 32, 160, 320, FAKE, 3, None, None) == B.EINVAL      # source slab shorter than T rows
+    assert kv(FAKE, FAR, 4, 10, 32, 320, 64, FAKE, 3, None, None) == B.EINVAL       # destination slab shorter than R rows
+    assert kv(FAKE, FAR, 4, 10, 32, 320, 320, FAKE, 11, None, None) == B.EINVAL     # R > T
+    assert kv(FAKE, FAR, 4, 10, 32, 320, 320, None, 3, None, None) == B.EINVAL      # no index list
+    assert kv(FAKE, FAKE, 4, 10, 32, 320, 320, FAKE, 3, None, None) == B.EINVAL     # in place
+    assert kv(FAKE, FAR, 4, 10, 32, 320, 320, FAKE, -1, None, None) == B.EINVAL     # device count missing
+    assert kv(FAKE, FAR, 0, 10, 32, 320, 320, FAKE, 3, None, None) == B.OK          # empty cache
+    assert kv(FAKE, FAR, 4, 10, 32, 320, 320, FAKE, 0, None, None) == B.OK          # nothing retained
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

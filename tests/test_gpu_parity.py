@@ -307,3 +307,39 @@ def test_balanced_split_forward_backward(w, r_host):
     a, b = f64_of(out)[idx], f64_of(out2)[idx]
     assert rel_l2(a, b) < 1e-2
     assert rel_l2(f64_of(gh)[idx], f64_of(gh2)[idx]) < 1e-2
+
+
+KV_CASES = [
+    # (leading dims, T, D, keep probability, destination capacity: "packed" or "prefill")
+    ((3, 2, 4), 777, 128, 0.25, "packed"),      # layers x key/value x heads, LLaMA head size
+    ((2, 2, 8), 616, 128, 0.30, "prefill"),     # compacted cache keeps the prefill capacity
+    ((5,), 1000, 8, 0.5, "packed"),             # 16-byte rows
+    ((70000,), 6, 8, 0.5, "packed"),            # more slabs than one grid dimension holds
+    ((1, 1), 300, 1024, 1.0, "packed"),         # nothing skipped
+]
+
+
+@pytest.mark.parametrize("lead,T,D,keep,cap", KV_CASES, ids=lambda v: str(v).replace(" ", ""))
+@pytest.mark.parametrize("r_host", [True, False], ids=["R-host", "R-device"])
+def test_skip_kv_cache_whole_cache(lead, T, D, keep, cap, r_host):
+    """Section 4.3 on a whole cache in one launch, bit for bit against the oracle."""
+    rng = np.random.default_rng(31 + T)
+    cache = rng.integers(0, 65536, lead + (T, D)).astype(np.uint16)
+    m = (rng.random(T) >= keep).astype(np.uint8)
+    want = O.kv_skip_cache_all(cache, m)
+    R = want.shape[-2]
+    mask = torch.from_numpy(m).cuda()
+    idx = torch.empty(T, dtype=torch.int32, device="cuda")
+    nret = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(B.skipffn_compact_workspace_bytes(T), 16), dtype=torch.uint8, device="cuda")
+    B.skipffn_compact(mask, idx, nret, None, ws)
+    src = to_dev_bf16(cache)
+    rcap = T if (cap == "prefill" or not r_host) else R
+    dst = torch.full(lead + (rcap, D), -1.0, dtype=torch.bfloat16, device="cuda")
+    B.skipffn_kv_compact(src, dst, idx, R if r_host else None, num_retained=nret)
+    torch.cuda.synchronize()
+    got = bits_of(dst)
+    assert np.array_equal(got[..., :R, :], want)
+    # rows past R are left as they were
+    assert np.all(got[..., R:, :] == bits_of(torch.full((1,), -1.0, dtype=torch.bfloat16))[0])
+

@@ -85,3 +85,24 @@ def test_kv_skip_cache_is_row_selection():
     assert kept.shape[0] == len(rows)
     for a, b in zip(kept, rows):
         assert np.array_equal(a, b)
+
+
+def test_kv_skip_cache_all_is_the_set_difference_of_every_slab():
+    """Section 4.3: the compacted cache is the cache minus the rows of skipped tokens.  The
+    oracle gathers retained rows; deleting the skipped rows (numpy.delete) is the same set
+    difference written the other way round, and a plain loop checks one slab row by row."""
+    rng = np.random.default_rng(9)
+    L, H, T, D = 3, 4, 57, 8
+    cache = rng.integers(0, 65536, (L, 2, H, T, D)).astype(np.uint16)
+    skip = (rng.random(T) < 0.6).astype(np.uint8)
+    got = O.kv_skip_cache_all(cache, skip)
+    skipped_positions = np.flatnonzero(skip != 0)
+    want = np.delete(cache, skipped_positions, axis=-2)
+    assert got.shape == want.shape == (L, 2, H, T - len(skipped_positions), D)
+    assert np.array_equal(got, want)
+    rows = [cache[2, 1, 3, t] for t in range(T) if skip[t] == 0]
+    assert np.array_equal(got[2, 1, 3], np.stack(rows))
+    # nothing skipped / everything skipped
+    assert np.array_equal(O.kv_skip_cache_all(cache, np.zeros(T, np.uint8)), cache)
+    assert O.kv_skip_cache_all(cache, np.ones(T, np.uint8)).shape == (L, 2, H, 0, D)
+
