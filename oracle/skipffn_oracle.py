@@ -226,8 +226,10 @@ def skipffn_backward_real(hidden, skip, w_gate, w_up, w_down, grad_out,
       dW_gate = dG^T xn ; dW_up = dU^T xn ; dxn = dG W_gate + dU W_up
       with xh = x * rstd, dxh = dxn * g :
       dx = rstd * (dxh - xh * mean_c(dxh * xh)) ; dX = dY + dx
-    Returns dict: dx [T, C], dw_gate [I, C], dw_up [I, C], dw_down [C, I] and
-    the intermediates dH, dG, dU, dxn on retained rows.
+      dgain = sum_r dxn * xh   (n(x) = xh * g is linear in the gain; with gain=None
+      this is the gradient at g = 1)
+    Returns dict: dx [T, C], dw_gate [I, C], dw_up [I, C], dw_down [C, I],
+    dgain [C] and the intermediates dH, dG, dU, dxn on retained rows.
     """
     hidden = np.asarray(hidden, dtype=np.float64)
     grad_out = np.asarray(grad_out, dtype=np.float64)
@@ -250,11 +252,12 @@ def skipffn_backward_real(hidden, skip, w_gate, w_up, w_down, grad_out,
     dxh = dxn if gain is None else dxn * gain[None, :]
     proj = np.sum(dxh * xh, axis=1) / C
     dx_norm = f["rstd"][:, None] * (dxh - xh * proj[:, None])
+    dgain = np.sum(dxn * xh, axis=0)                     # [C]
 
     dx = grad_out.copy()                                 # skipped: identity
     dx[idx] = dY + dx_norm
     return {"dx": dx, "dw_gate": dw_gate, "dw_up": dw_up, "dw_down": dw_down,
-            "dH": dH, "dG": dG, "dU": dU, "dxn": dxn, "idx": idx, "R": R}
+            "dgain": dgain, "dH": dH, "dG": dG, "dU": dU, "dxn": dxn, "idx": idx, "R": R}
 
 
 # --------------------------------------------------------------------------
@@ -296,7 +299,7 @@ def skipffn_backward(hidden_bits, skip, w_gate_bits, w_up_bits, w_down_bits,
     """Backward of one Skip-FFN block on bf16 data.
 
     Returns dict: dx_bits uint16 [T, C] (skipped rows are byte copies of
-    grad_out), float64 dw_gate / dw_up / dw_down (round them with
+    grad_out), float64 dw_gate / dw_up / dw_down / dgain (round them with
     f64_to_bf16_bits or f64_to_f32 to the dtype being compared), and the
     float64 intermediates dH, dG, dU, dxn.
     """
@@ -314,7 +317,7 @@ def skipffn_backward(hidden_bits, skip, w_gate_bits, w_up_bits, w_down_bits,
     dx_bits = grad_out_bits.copy()
     dx_bits[idx] = f64_to_bf16_bits(sub["dx"])
     return {"dx_bits": dx_bits, "dw_gate": sub["dw_gate"], "dw_up": sub["dw_up"],
-            "dw_down": sub["dw_down"], "dH": sub["dH"], "dG": sub["dG"],
+            "dw_down": sub["dw_down"], "dgain": sub["dgain"], "dH": sub["dH"], "dG": sub["dG"],
             "dU": sub["dU"], "dxn": sub["dxn"], "idx": idx, "R": R}
 
 

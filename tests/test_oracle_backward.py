@@ -39,6 +39,8 @@ def test_finite_differences(seed, gain):
         assert err < 1e-7, (name, err)
 
     fd(x, "dx"); fd(wg, "dw_gate"); fd(wu, "dw_up"); fd(wd, "dw_down")
+    if g is not None:
+        fd(g, "dgain")
 
 
 @pytest.mark.parametrize("gain", [True, False])
@@ -51,7 +53,8 @@ def test_against_torch_autograd(gain):
 
     xt = torch.tensor(x, requires_grad=True)
     tg, tu, td = (torch.tensor(a, requires_grad=True) for a in (wg, wu, wd))
-    gt = None if g is None else torch.tensor(g)
+    # without a gain the oracle reports the gradient at g = 1
+    gt = torch.tensor(np.ones(C) if g is None else g, requires_grad=True)
     keep = torch.tensor(skip == 0)
     xr = xt[keep]
     n = F.rms_norm(xr, (C,), gt, 1e-5)
@@ -59,7 +62,7 @@ def test_against_torch_autograd(gain):
     out = xt.clone()
     out[keep] = xr + y
     (out * torch.tensor(gout)).sum().backward()
-    for name, t in (("dx", xt), ("dw_gate", tg), ("dw_up", tu), ("dw_down", td)):
+    for name, t in (("dx", xt), ("dw_gate", tg), ("dw_up", tu), ("dw_down", td), ("dgain", gt)):
         assert np.allclose(mine[name], t.grad.numpy(), rtol=1e-11, atol=1e-12), name
 
 
