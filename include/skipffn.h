@@ -118,8 +118,10 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps,
  *       SKIPFFN_FLAG_DW_FP32 (float32) / SKIPFFN_FLAG_DW_ACCUMULATE (+=).
  *       With R == 0 they are zero-filled (or left as they are when
  *       accumulating).
- *   workspace: at least skipffn_backward_workspace_bytes(R_max, C, I)
- * No gradient for rms_gain is produced. */
+ *   d_rms_gain  NULL, or float32 [C] OUT: gradient of the RMSNorm gain (of an all-ones gain
+ *       when rms_gain is NULL), overwritten or += like dw_*; always float32.  It is summed
+ *       over rows in a fixed order (deterministic).
+ *   workspace: at least skipffn_backward_workspace_bytes(R_max, C, I) */
 size_t skipffn_backward_workspace_bytes(int64_t R_max, int64_t C, int64_t I);
 int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps,
                      const void* grad_out, void* grad_hidden,
@@ -127,7 +129,7 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps,
                      const void* rms_gain,
                      const void* w_gate, const void* w_up, const void* w_down,
                      const void* saved,
-                     void* dw_gate, void* dw_up, void* dw_down,
+                     void* dw_gate, void* dw_up, void* dw_down, void* d_rms_gain,
                      void* workspace, size_t workspace_bytes,
                      uint32_t flags, void* stream);
 

@@ -38,7 +38,7 @@ _SIGNATURES = {
     "skipffn_backward_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
     "skipffn_backward": (c_int, [c_int64, c_int64, c_int64, c_float, c_void_p, c_void_p,
                                  c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                 c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                  c_size_t, c_uint32, c_void_p]),
     "skipffn_gather_rows": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_void_p, c_int64,
                                     c_void_p, c_void_p]),
@@ -152,7 +152,7 @@ def skipffn_forward(hidden, out, idx, R, w_gate, w_up, w_down, *, eps=1e-5, rms_
 
 def skipffn_backward(grad_out, grad_hidden, idx, R, w_gate, w_up, w_down, saved, dw_gate, dw_up,
                      dw_down, *, eps=1e-5, rms_gain=None, num_retained=None, workspace=None,
-                     flags=0):
+                     flags=0, d_rms_gain=None):
     T, C = grad_out.shape
     I = w_gate.shape[0]
     Rv, nr = _rargs(R, num_retained)
@@ -160,7 +160,7 @@ def skipffn_backward(grad_out, grad_hidden, idx, R, w_gate, w_up, w_down, saved,
     _check(lib().skipffn_backward(T, C, I, eps, _ptr(grad_out), _ptr(grad_hidden), _ptr(idx), Rv,
                                   nr, _ptr(rms_gain), _ptr(w_gate), _ptr(w_up), _ptr(w_down),
                                   _ptr(saved), _ptr(dw_gate), _ptr(dw_up), _ptr(dw_down),
-                                  _ptr(workspace), ws_bytes, flags, _stream()),
+                                  _ptr(d_rms_gain), _ptr(workspace), ws_bytes, flags, _stream()),
            "skipffn_backward")
 
 

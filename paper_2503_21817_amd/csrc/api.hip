@@ -102,7 +102,7 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     return w;
 }
 
-struct BwdWs { size_t dy, dyT, dg, du, partial, total; };
+struct BwdWs { size_t dy, dyT, dg, du, partial, gainp, total; };
 BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
     BwdWs w; size_t o = 0;
     w.dy = o; o += align_up((size_t)R * C * 2);
@@ -110,6 +110,7 @@ BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
     w.dg = o; o += align_up((size_t)R * I * 2);
     w.du = o; o += align_up((size_t)R * I * 2);
     w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
+    w.gainp = o; o += align_up(gain_partial_bytes(R, C));
     w.total = o;
     return w;
 }
@@ -371,11 +372,12 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
                      void* grad_hidden, const int32_t* idx, int64_t R,
                      const int32_t* num_retained, const void* rms_gain, const void* w_gate,
                      const void* w_up, const void* w_down, const void* saved, void* dw_gate,
-                     void* dw_up, void* dw_down, void* workspace, size_t workspace_bytes,
-                     uint32_t flags, void* stream) {
+                     void* dw_up, void* dw_down, void* d_rms_gain, void* workspace,
+                     size_t workspace_bytes, uint32_t flags, void* stream) {
     int st = check_common(T, C, I, R, num_retained, flags);
     if (st != SKIPFFN_OK) return st;
     (void)eps;
+    if (d_rms_gain != nullptr && !aligned16(d_rms_gain)) return SKIPFFN_EINVAL;
     const int64_t Rb = R < 0 ? T : R;
     if (T > 0 && (bad_ptr(grad_out) || bad_ptr(grad_hidden))) return SKIPFFN_EINVAL;
     if (T > 0 && partial_overlap(grad_out, grad_hidden, (size_t)T * C * 2)) return SKIPFFN_EINVAL;
@@ -405,6 +407,8 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
             if ((e = launch_fill_zero(dw_gate, wbytes, s)) != hipSuccess) return hip_fail(e);
             if ((e = launch_fill_zero(dw_up, wbytes, s)) != hipSuccess) return hip_fail(e);
             if ((e = launch_fill_zero(dw_down, wbytes, s)) != hipSuccess) return hip_fail(e);
+            if (d_rms_gain != nullptr &&
+                (e = launch_fill_zero(d_rms_gain, (size_t)C * 4, s)) != hipSuccess) return hip_fail(e);
         }
         return SKIPFFN_OK;
     }
@@ -493,7 +497,9 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     // RMSNorm backward + residual gradient, scattered to the retained rows
     e = launch_rmsnorm_bwd_scatter(partial, pl, (int)Rb, r_dev, (int)C, xrows, rstd,
                                    static_cast<const bf16_t*>(rms_gain), dY, idx,
-                                   static_cast<bf16_t*>(grad_hidden), s);
+                                   static_cast<bf16_t*>(grad_hidden),
+                                   reinterpret_cast<float*>(ws + W.gainp),
+                                   static_cast<float*>(d_rms_gain), accum ? 1 : 0, s);
     if (e != hipSuccess) return hip_fail(e);
     return SKIPFFN_OK;
 }

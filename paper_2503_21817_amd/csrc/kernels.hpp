@@ -64,11 +64,15 @@ hipError_t launch_gather_transpose(const bf16_t* src, int C, const int32_t* idx,
 // copy every row t of src to dst that is NOT listed in idx (skipped tokens)
 hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row_bytes,
                               const int32_t* idx, int R, const int32_t* r_dev, hipStream_t s);
-// dX[idx[r]] = bf16(dY[r] + rmsnorm_bwd(sum_z dxn_partial[z][r], x[r], rstd[r], gain))
+// dX[idx[r]] = bf16(dY[r] + rmsnorm_bwd(sum_z dxn_partial[z][r], x[r], rstd[r], gain)); with dgain != null
+// also dgain[c] (+)= sum_r dxn[r][c] * x[r][c] * rstd[r] (fp32, through gain_partial)
 hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl, int R,
                                       const int32_t* r_dev, int C, const bf16_t* xrows,
                                       const float* rstd, const bf16_t* gain, const bf16_t* dY,
-                                      const int32_t* idx, bf16_t* dX, hipStream_t s);
+                                      const int32_t* idx, bf16_t* dX, float* gain_partial,
+                                      float* dgain, int accumulate, hipStream_t s);
+// bytes of the gain-gradient scratch (one fp32 row of C per strip of rows)
+size_t gain_partial_bytes(int64_t R, int64_t C);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 // ---- GEMMs -----------------------------------------------------------------------

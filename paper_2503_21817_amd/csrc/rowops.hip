@@ -333,111 +333,204 @@ hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row
 //   dx = rstd * (dxh - xh * mean_c(dxh * xh));  dX[idx[r]] = bf16(dY[r] + dx)
 // dxn arrives as `splits` fp32 partial sums [z][r][c] (the split-K slabs of the
 // dG*W_gate + dU*W_up GEMM), added here in z order.
-template <bool IN_REGS>
+// With GAIN_GRAD a workgroup walks a strip of GAIN_STRIP rows and also accumulates the
+// gradient of the gain, dgain[c] = sum_r dxn[r][c] * x[r][c] * rstd[r], over its strip into
+// gpart[strip][c]; gain_grad_reduce_kernel adds the strips in order (deterministic).
+constexpr int GAIN_STRIP = 4;
+template <bool IN_REGS, bool GAIN_GRAD>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     const float* __restrict__ part, PartialLayout pl, int Rbound, const int32_t* __restrict__ r_dev,
     int C, const bf16_t* __restrict__ xrows, const float* __restrict__ rstd_in,
     const bf16_t* __restrict__ gain, const bf16_t* __restrict__ dY,
-    const int32_t* __restrict__ idx, bf16_t* dX) {
+    const int32_t* __restrict__ idx, bf16_t* dX, float* __restrict__ gpart) {
     __shared__ float red[4];
     const int R = effective_rows(Rbound, r_dev);
     const int tid = threadIdx.x;
-    const int r = blockIdx.x;
-    if (r >= R) return;                       // the whole workgroup leaves together
+    constexpr int STRIP = GAIN_GRAD ? GAIN_STRIP : 1;
+    const int r_begin = blockIdx.x * STRIP;
+    if (r_begin >= R) return;                 // the whole workgroup leaves together
+    const int r_end = r_begin + STRIP < R ? r_begin + STRIP : R;
     const int chunks = C >> 3;
-    const float rstd = rstd_in[r];
     const int64_t zstride = (int64_t)Rbound * C;
-    const float* p = part + (int64_t)r * C;
-    const int splits = partial_count(pl, R, r, 0);
-    const u32x4* xs = reinterpret_cast<const u32x4*>(xrows + (int64_t)r * C);
     const u32x4* gs = reinterpret_cast<const u32x4*>(gain);
+    constexpr int MAXV = 2;                   // register-resident row: C <= 256 * 8 * 2 = 4096
+    float gacc[IN_REGS ? MAXV : 1][8];
+    if (IN_REGS && GAIN_GRAD) {
+#pragma unroll
+        for (int v = 0; v < MAXV; ++v)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) gacc[v][j] = 0.0f;
+    }
+    float* gp = GAIN_GRAD ? gpart + (int64_t)blockIdx.x * C : nullptr;
 
-    auto load_dxh = [&](int c, float* d) {
+    for (int r = r_begin; r < r_end; ++r) {
+        const float rstd = rstd_in[r];
+        const float* p = part + (int64_t)r * C;
+        const u32x4* xs = reinterpret_cast<const u32x4*>(xrows + (int64_t)r * C);
+        const int splits = partial_count(pl, R, r, 0);
+        // d = dxn (sum of the split-K slabs)
+        auto load_dxn = [&](int c, float* d) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) d[j] = 0.0f;
-        for (int z = 0; z < splits; ++z) {
-            f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride + c * 8);
-            f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + c * 8 + 4);
+            for (int j = 0; j < 8; ++j) d[j] = 0.0f;
+            for (int z = 0; z < splits; ++z) {
+                f32x4 a = *reinterpret_cast<const f32x4*>(p + z * zstride + c * 8);
+                f32x4 b = *reinterpret_cast<const f32x4*>(p + z * zstride + c * 8 + 4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                d[j] += a[j];
-                d[4 + j] += b[j];
+                for (int j = 0; j < 4; ++j) {
+                    d[j] += a[j];
+                    d[4 + j] += b[j];
+                }
+            }
+        };
+        auto apply_gain = [&](int c, float* d) {
+            if (gain != nullptr) {
+                float g[8];
+                unpack8(gs[c], g);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) d[j] *= g[j];
+            }
+        };
+        const u32x4* dys = reinterpret_cast<const u32x4*>(dY + (int64_t)r * C);
+        u32x4* out = reinterpret_cast<u32x4*>(dX + (int64_t)idx[r] * C);
+        auto emit = [&](int c, const float* d, const float* x, const u32x4& dyraw, float dot) {
+            float gy[8], o[8];
+            unpack8(dyraw, gy);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] = gy[j] + rstd * (d[j] - (x[j] * rstd) * dot);
+            out[c] = pack8(o);
+        };
+
+        if (IN_REGS) {
+            // the row (sum of the split-K slabs, x and dY) is read once and kept in registers
+            float d[MAXV][8], x[MAXV][8];
+            u32x4 dyraw[MAXV];
+            float dot = 0.0f;
+#pragma unroll
+            for (int v = 0; v < MAXV; ++v) {
+                int c = tid + ROW_THREADS * v;
+                if (c < chunks) {
+                    load_dxn(c, d[v]);
+                    unpack8(xs[c], x[v]);
+                    dyraw[v] = dys[c];
+                    if (GAIN_GRAD) {
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) gacc[v][j] += d[v][j] * (x[v][j] * rstd);
+                    }
+                    apply_gain(c, d[v]);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) dot += d[v][j] * (x[v][j] * rstd);
+                }
+            }
+            dot = block_sum(dot, red) / (float)C;
+#pragma unroll
+            for (int v = 0; v < MAXV; ++v) {
+                int c = tid + ROW_THREADS * v;
+                if (c < chunks) emit(c, d[v], x[v], dyraw[v], dot);
+            }
+        } else {
+            float dot = 0.0f;
+            for (int c = tid; c < chunks; c += ROW_THREADS) {
+                float d[8], x[8];
+                load_dxn(c, d);
+                unpack8(xs[c], x);
+                if (GAIN_GRAD) {
+                    // the strip's partial lives in global memory: each thread owns its chunks
+                    f32x4* g0 = reinterpret_cast<f32x4*>(gp + c * 8);
+                    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
+                    if (r > r_begin) { lo = g0[0]; hi = g0[1]; }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        lo[j] += d[j] * (x[j] * rstd);
+                        hi[j] += d[4 + j] * (x[4 + j] * rstd);
+                    }
+                    g0[0] = lo; g0[1] = hi;
+                }
+                apply_gain(c, d);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) dot += d[j] * (x[j] * rstd);
+            }
+            dot = block_sum(dot, red) / (float)C;
+            for (int c = tid; c < chunks; c += ROW_THREADS) {
+                float d[8], x[8];
+                load_dxn(c, d);
+                apply_gain(c, d);
+                unpack8(xs[c], x);
+                emit(c, d, x, dys[c], dot);
             }
         }
-        if (gain != nullptr) {
-            float g[8];
-            unpack8(gs[c], g);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) d[j] *= g[j];
-        }
-    };
-    const u32x4* dys = reinterpret_cast<const u32x4*>(dY + (int64_t)r * C);
-    u32x4* out = reinterpret_cast<u32x4*>(dX + (int64_t)idx[r] * C);
-    auto emit = [&](int c, const float* d, const float* x, const u32x4& dyraw, float dot) {
-        float gy[8], o[8];
-        unpack8(dyraw, gy);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = gy[j] + rstd * (d[j] - (x[j] * rstd) * dot);
-        out[c] = pack8(o);
-    };
-
-    if (IN_REGS) {
-        // the row (sum of the split-K slabs, x and dY) is read once and kept in registers
-        constexpr int MAXV = 2;          // C <= 256 * 8 * 2 = 4096
-        float d[MAXV][8], x[MAXV][8];
-        u32x4 dyraw[MAXV];
-        float dot = 0.0f;
+        if (STRIP > 1) __syncthreads();       // `red` is reused by the next row
+    }
+    if (IN_REGS && GAIN_GRAD) {
 #pragma unroll
         for (int v = 0; v < MAXV; ++v) {
             int c = tid + ROW_THREADS * v;
             if (c < chunks) {
-                load_dxh(c, d[v]);
-                unpack8(xs[c], x[v]);
-                dyraw[v] = dys[c];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) dot += d[v][j] * (x[v][j] * rstd);
+                f32x4* g0 = reinterpret_cast<f32x4*>(gp + c * 8);
+                f32x4 lo = {gacc[v][0], gacc[v][1], gacc[v][2], gacc[v][3]};
+                f32x4 hi = {gacc[v][4], gacc[v][5], gacc[v][6], gacc[v][7]};
+                g0[0] = lo; g0[1] = hi;
             }
         }
-        dot = block_sum(dot, red) / (float)C;
-#pragma unroll
-        for (int v = 0; v < MAXV; ++v) {
-            int c = tid + ROW_THREADS * v;
-            if (c < chunks) emit(c, d[v], x[v], dyraw[v], dot);
-        }
-    } else {
-        float dot = 0.0f;
-        for (int c = tid; c < chunks; c += ROW_THREADS) {
-            float d[8], x[8];
-            load_dxh(c, d);
-            unpack8(xs[c], x);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) dot += d[j] * (x[j] * rstd);
-        }
-        dot = block_sum(dot, red) / (float)C;
-        for (int c = tid; c < chunks; c += ROW_THREADS) {
-            float d[8], x[8];
-            load_dxh(c, d);
-            unpack8(xs[c], x);
-            emit(c, d, x, dys[c], dot);
-        }
+    }
+}
+
+// dgain[c] (+)= sum over strips of gpart[strip][c], strips added in ascending order by four
+// interleaved partial sums (fixed association).  64 columns per workgroup.
+__global__ __launch_bounds__(ROW_THREADS) void gain_grad_reduce_kernel(
+    const float* __restrict__ gpart, int Rbound, const int32_t* __restrict__ r_dev, int C,
+    float* __restrict__ dgain, int accumulate) {
+    __shared__ float part4[4][64];
+    const int R = effective_rows(Rbound, r_dev);
+    const int nstrips = (R + GAIN_STRIP - 1) / GAIN_STRIP;
+    const int cx = threadIdx.x & 63, sy = threadIdx.x >> 6;
+    const int c = blockIdx.x * 64 + cx;
+    float acc = 0.0f;
+    if (c < C)
+        for (int sidx = sy; sidx < nstrips; sidx += 4) acc += gpart[(int64_t)sidx * C + c];
+    part4[sy][cx] = acc;
+    __syncthreads();
+    if (sy == 0 && c < C) {
+        float v = (part4[0][cx] + part4[1][cx]) + (part4[2][cx] + part4[3][cx]);
+        dgain[c] = accumulate ? dgain[c] + v : v;
     }
 }
 
 hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl, int R,
                                       const int32_t* r_dev, int C, const bf16_t* xrows,
                                       const float* rstd, const bf16_t* gain, const bf16_t* dY,
-                                      const int32_t* idx, bf16_t* dX, hipStream_t s) {
+                                      const int32_t* idx, bf16_t* dX, float* gain_partial,
+                                      float* dgain, int accumulate, hipStream_t s) {
     if (R <= 0) return hipSuccess;
-    dim3 grid(R), block(ROW_THREADS);
+    const bool gg = dgain != nullptr;
+    dim3 grid(gg ? (R + GAIN_STRIP - 1) / GAIN_STRIP : R), block(ROW_THREADS);
     profile_mark_begin(KC_RMSNORM_BWD, s);
-    if (C <= 4096)
-        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<true>, grid, block, 0, s, dxn_partial, pl,
-                           R, r_dev, C, xrows, rstd, gain, dY, idx, dX);
-    else
-        hipLaunchKernelGGL(rmsnorm_bwd_scatter_kernel<false>, grid, block, 0, s, dxn_partial, pl,
-                           R, r_dev, C, xrows, rstd, gain, dY, idx, dX);
+    if (C <= 4096) {
+        if (gg)
+            hipLaunchKernelGGL((rmsnorm_bwd_scatter_kernel<true, true>), grid, block, 0, s, dxn_partial,
+                               pl, R, r_dev, C, xrows, rstd, gain, dY, idx, dX, gain_partial);
+        else
+            hipLaunchKernelGGL((rmsnorm_bwd_scatter_kernel<true, false>), grid, block, 0, s, dxn_partial,
+                               pl, R, r_dev, C, xrows, rstd, gain, dY, idx, dX, gain_partial);
+    } else {
+        if (gg)
+            hipLaunchKernelGGL((rmsnorm_bwd_scatter_kernel<false, true>), grid, block, 0, s, dxn_partial,
+                               pl, R, r_dev, C, xrows, rstd, gain, dY, idx, dX, gain_partial);
+        else
+            hipLaunchKernelGGL((rmsnorm_bwd_scatter_kernel<false, false>), grid, block, 0, s, dxn_partial,
+                               pl, R, r_dev, C, xrows, rstd, gain, dY, idx, dX, gain_partial);
+    }
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && gg) {
+        hipLaunchKernelGGL(gain_grad_reduce_kernel, dim3((C + 63) / 64), block, 0, s, gain_partial, R,
+                           r_dev, C, dgain, accumulate);
+        e = hipGetLastError();
+    }
     profile_mark_end(KC_RMSNORM_BWD, s);
-    return hipGetLastError();
+    return e;
+}
+
+size_t gain_partial_bytes(int64_t R, int64_t C) {
+    return (size_t)((R + GAIN_STRIP - 1) / GAIN_STRIP) * (size_t)C * 4;
 }
 
 // ---- zero fill (a kernel, so that it can be captured in a HIP graph) -----------------------

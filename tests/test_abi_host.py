@@ -63,9 +63,9 @@ def fwd(T=8, C=64, I=128, eps=1e-5, hidden=FAKE, out=FAKE, idx=FAKE, R=4, nr=Non
 
 
 def bwd(T=8, C=64, I=128, go=FAKE, gh=FAKE, idx=FAKE, R=4, nr=None, wg=FAKE, wu=FAKE, wd=FAKE,
-        saved=FAKE, dwg=FAKE, dwu=FAKE, dwd=FAKE, ws=FAKE, ws_bytes=1 << 40, flags=0):
+        saved=FAKE, dwg=FAKE, dwu=FAKE, dwd=FAKE, dgain=None, ws=FAKE, ws_bytes=1 << 40, flags=0):
     return B.lib().skipffn_backward(T, C, I, 1e-5, go, gh, idx, R, nr, None, wg, wu, wd, saved,
-                                    dwg, dwu, dwd, ws, ws_bytes, flags, None)
+                                    dwg, dwu, dwd, dgain, ws, ws_bytes, flags, None)
 
 
 def test_forward_rejects_bad_arguments_on_the_host():
@@ -103,6 +103,7 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert bwd(dwd=ODD) == B.EINVAL
     assert bwd(flags=0x10) == B.EUNSUPPORTED
     assert bwd(ws_bytes=0) == B.EWORKSPACE
+    assert bwd(dgain=ODD) == B.EINVAL
 
 
 def test_compact_and_gather_reject_bad_arguments_on_the_host():

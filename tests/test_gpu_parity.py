@@ -75,7 +75,7 @@ def gpu_forward(p, R_host=True, inplace=False, saved=True, flags=0):
     return out, bufs
 
 
-def gpu_backward(p, bufs, R_host=True, inplace=False, flags=0, dw=None):
+def gpu_backward(p, bufs, R_host=True, inplace=False, flags=0, dw=None, dgain=None):
     w = p.w
     grad = p.d_grad.clone()
     gh = grad if inplace else torch.full_like(grad, float("nan"))
@@ -86,7 +86,8 @@ def gpu_backward(p, bufs, R_host=True, inplace=False, flags=0, dw=None):
               torch.full((w.C, w.I), float("nan"), dtype=dt, device="cuda")]
     B.skipffn_backward(grad, gh, bufs.idx, w.R if R_host else None, p.d_wg, p.d_wu, p.d_wd,
                        bufs.saved, dw[0], dw[1], dw[2], eps=w.eps, rms_gain=p.d_gain,
-                       num_retained=bufs.num_retained, workspace=bufs.bwd_ws, flags=flags)
+                       num_retained=bufs.num_retained, workspace=bufs.bwd_ws, flags=flags,
+                       d_rms_gain=dgain)
     torch.cuda.synchronize()
     return gh, dw
 
@@ -342,4 +343,54 @@ def test_skip_kv_cache_whole_cache(lead, T, D, keep, cap, r_host):
     assert np.array_equal(got[..., :R, :], want)
     # rows past R are left as they were
     assert np.all(got[..., R:, :] == bits_of(torch.full((1,), -1.0, dtype=torch.bfloat16))[0])
+
+
+GAIN_CASES = [
+    W.small(C=512, I=1368, visual=(300, 411), text=(20, 35), keep=(130, 212), seed=41, name="gain-2tiles"),
+    W.small(C=264, I=520, visual=(700,), text=(9,), keep=(600,), seed=42, name="gain-odd-dims"),
+    W.small(C=1024, I=256, visual=(64,), text=(1,), keep=(0,), seed=43, name="gain-one-row"),
+    W.small(C=4104, I=128, visual=(40,), text=(3,), keep=(19,), seed=44, name="gain-wide-row"),   # C > 4096: streaming path
+]
+
+
+@pytest.mark.parametrize("w", GAIN_CASES, ids=lambda w: w.name)
+@pytest.mark.parametrize("with_gain", [True, False], ids=["gain", "unit-gain"])
+def test_rmsnorm_gain_gradient(w, with_gain):
+    """d_rms_gain against the oracle (the gradient at g = 1 when no gain tensor is given);
+    asking for it must not change dX; accumulate adds to what is there; R on the device."""
+    p = Problem(w, unit_gain=not with_gain, with_gain_tensor=with_gain)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    idx = bo["idx"]
+    _, bufs = gpu_forward(p)
+    gh0, _ = gpu_backward(p, bufs)
+    dgain = torch.full((w.C,), float("nan"), dtype=torch.float32, device="cuda")
+    gh1, _ = gpu_backward(p, bufs, dgain=dgain)
+    got = dgain.double().cpu().numpy()
+    assert rel_l2(got, bo["dgain"]) < REL_L2_TOL
+    assert rel_l2(f64_of(gh1)[idx], f64_of(gh0)[idx]) < 1e-6      # same sums, same order
+    # deterministic: a second run gives the same bits
+    dgain2 = torch.zeros_like(dgain)
+    gpu_backward(p, bufs, dgain=dgain2)
+    assert torch.equal(dgain, dgain2)
+    # accumulate
+    acc = torch.ones_like(dgain)
+    dwa = [torch.zeros((w.I, w.C), dtype=torch.bfloat16, device="cuda"),
+           torch.zeros((w.I, w.C), dtype=torch.bfloat16, device="cuda"),
+           torch.zeros((w.C, w.I), dtype=torch.bfloat16, device="cuda")]
+    gpu_backward(p, bufs, flags=B.FLAG_DW_ACCUMULATE, dw=dwa, dgain=acc)
+    assert rel_l2(acc.double().cpu().numpy() - 1.0, bo["dgain"]) < REL_L2_TOL
+    # R read on the device
+    _, bufs_d = gpu_forward(p, R_host=False)
+    dgain_d = torch.full((w.C,), float("nan"), dtype=torch.float32, device="cuda")
+    gpu_backward(p, bufs_d, R_host=False, dgain=dgain_d)
+    assert rel_l2(dgain_d.double().cpu().numpy(), bo["dgain"]) < REL_L2_TOL
+
+
+def test_gain_gradient_with_nothing_retained_is_zero():
+    w = W.small(C=256, I=512, visual=(50,), text=(0,), keep=(0,), seed=45, name="gain-empty")
+    p = Problem(w)
+    _, bufs = gpu_forward(p)
+    dgain = torch.full((w.C,), 7.0, dtype=torch.float32, device="cuda")
+    gpu_backward(p, bufs, dgain=dgain)
+    assert torch.count_nonzero(dgain).item() == 0
 
