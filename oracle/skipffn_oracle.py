@@ -343,3 +343,76 @@ def kv_skip_cache_all(cache_bits, skip):
     R = out[0].shape[0] if out else int((np.asarray(skip) == 0).sum())
     return np.stack(out).reshape(lead + (R, c.shape[-1])) if out else np.zeros(lead + (R, c.shape[-1]), c.dtype)
 
+
+# --------------------------------------------------------------------------
+# Adaptive summary layer (Section 4.2, the summary-token equation):
+#   x^s = softmax(X W^T)^T X,   X [n, C] a set of visual tokens, W [1, C],
+# the softmax taken over the n tokens.  One summary row per token set.
+# --------------------------------------------------------------------------
+
+def summary_forward_real(X, w):
+    """X float64 [n, C], w float64 [C] -> dict: xs [C], p [n] (softmax weights),
+    s [n] (scores X w) and lse (log-sum-exp of s).  n >= 1."""
+    X = np.asarray(X, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    s = X @ w                                   # [n] : X W^T
+    m = np.max(s)
+    e = np.exp(s - m)
+    p = e / np.sum(e)                           # softmax over tokens
+    xs = p @ X                                  # (softmax)^T X
+    return {"xs": xs, "p": p, "s": s, "lse": m + np.log(np.sum(e))}
+
+
+def summary_backward_real(X, w, g):
+    """Gradients of L = sum(x^s * g): with dp = X g and ds = p * (dp - p . dp)
+    (softmax Jacobian),  dX = p g^T + ds w^T,  dw = X^T ds."""
+    X = np.asarray(X, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    f = summary_forward_real(X, w)
+    p = f["p"]
+    dp = X @ g                                  # [n]
+    ds = p * (dp - np.dot(p, dp))
+    dX = np.outer(p, g) + np.outer(ds, w)
+    dw = X.T @ ds
+    return {"dX": dX, "dw": dw, "ds": ds, "dp": dp}
+
+
+def summary_forward(hidden_bits, tok, seg, w_bits):
+    """bf16 interface over S token sets: set i is the rows tok[seg[i]:seg[i+1]] of
+    hidden_bits [T, C].  Returns out_bits uint16 [S, C] (each summary rounded once),
+    float64 xs [S, C], scores [n_tok] and lse [S]."""
+    tok = np.asarray(tok, dtype=np.int64)
+    seg = np.asarray(seg, dtype=np.int64)
+    w = bf16_bits_to_f64(w_bits)
+    S = len(seg) - 1
+    C = np.asarray(hidden_bits).shape[1]
+    xs = np.zeros((S, C))
+    scores = np.zeros(len(tok))
+    lse = np.zeros(S)
+    for i in range(S):
+        rows = tok[seg[i]:seg[i + 1]]
+        f = summary_forward_real(bf16_bits_to_f64(np.asarray(hidden_bits)[rows]), w)
+        xs[i] = f["xs"]
+        scores[seg[i]:seg[i + 1]] = f["s"]
+        lse[i] = f["lse"]
+    return {"out_bits": f64_to_bf16_bits(xs), "xs": xs, "scores": scores, "lse": lse}
+
+
+def summary_backward(hidden_bits, tok, seg, w_bits, grad_out_bits, grad_hidden_bits):
+    """Backward over S disjoint token sets: returns gh_bits uint16 [T, C] =
+    bf16(grad_hidden + dX) on the listed rows (other rows are byte copies) and
+    float64 dw [C] summed over the sets."""
+    tok = np.asarray(tok, dtype=np.int64)
+    seg = np.asarray(seg, dtype=np.int64)
+    w = bf16_bits_to_f64(w_bits)
+    hb = np.asarray(hidden_bits)
+    gh_bits = np.array(grad_hidden_bits, dtype=np.uint16, copy=True)
+    dw = np.zeros(hb.shape[1])
+    for i in range(len(seg) - 1):
+        rows = tok[seg[i]:seg[i + 1]]
+        b = summary_backward_real(bf16_bits_to_f64(hb[rows]), w, bf16_bits_to_f64(np.asarray(grad_out_bits)[i]))
+        gh_bits[rows] = f64_to_bf16_bits(bf16_bits_to_f64(gh_bits[rows]) + b["dX"])
+        dw += b["dw"]
+    return {"gh_bits": gh_bits, "dw": dw}
+
