@@ -45,12 +45,13 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
                          "(32 layers x key/value x 8 heads x 128) for the token mixes of configurations "
-                         "2, 3 and 5.  The JSON line then carries a 'sweep' array")
+                         "2, 3 and 5; summary: the adaptive summary layer, forward and backward, on "
+                         "the visual token sets of the same mixes.  The JSON line then carries a 'sweep' array")
     ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
@@ -217,6 +218,55 @@ def compact_sweep(torch, B, args):
             "config": {"workload": "mask compaction, 25 % retained, T = 2^13 .. 2^26"}, "sweep": rows}
 
 
+def summary_sweep(torch, B, W, args):
+    """Adaptive summary layer (Section 4.2): per sequence one summary of the retained and one
+    of the skipped visual tokens.  Algorithmic bytes: forward reads the listed rows once
+    (n_tok * C * 2); backward reads them and reads + writes their gradient rows (3x)."""
+    rows = []
+    for cfg in (2, 3, 5):
+        w = W.config(cfg)
+        T, C = w.T, w.C
+        tok_np, seg_np = W.make_summary_sets(w)
+        n_tok, S = len(tok_np), len(seg_np) - 1
+        g = torch.Generator(device="cuda")
+        g.manual_seed(600 + cfg)
+        hid = torch.randn((T, C), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        gh = torch.randn((T, C), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        gout = torch.randn((S, C), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        wv = torch.from_numpy(W.make_summary_weight(w).view(np.int16)).cuda().view(torch.bfloat16)
+        tok = torch.from_numpy(tok_np).cuda()
+        seg = torch.from_numpy(seg_np).cuda()
+        out = torch.empty((S, C), dtype=torch.bfloat16, device="cuda")
+        dw = torch.empty(C, dtype=torch.float32, device="cuda")
+        sv = torch.empty(B.skipffn_summary_saved_bytes(n_tok, S, C), dtype=torch.uint8, device="cuda")
+        ws = torch.empty(B.skipffn_summary_workspace_bytes(n_tok, S, C), dtype=torch.uint8, device="cuda")
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+        ms_f = timed(lambda: B.skipffn_summary_forward(hid, tok, seg, wv, out, saved=sv, workspace=ws))
+        ms_b = timed(lambda: B.skipffn_summary_backward(hid, tok, seg, wv, sv, gout, gh, dw, workspace=ws))
+        bf, bb = n_tok * C * 2, 3 * n_tok * C * 2
+        rows.append({"workload": w.name, "n_tok": n_tok, "sets": S,
+                     "fwd_us": round(ms_f * 1e3, 1), "fwd_gbs": round(bf / (ms_f * 1e-3) / 1e9, 1),
+                     "bwd_us": round(ms_b * 1e3, 1), "bwd_gbs": round(bb / (ms_b * 1e-3) / 1e9, 1),
+                     "fwd_frac_hbm_peak": round(bf / (ms_f * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "bwd_frac_hbm_peak": round(bb / (ms_b * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)})
+    return {"metric": "adaptive summary layer bandwidth", "unit": "GB/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "dtype": "bf16 in, f32 arithmetic",
+            "data": "synthetic",
+            "config": {"workload": "retained and skipped visual token sets of configurations 2, 3, 5, C=4096"},
+            "sweep": rows}
+
+
 def kv_sweep(torch, B, W, args):
     """Skip KV-cache (Section 4.3) on a packed cache [layers, 2, kv heads, T, head dim] of the
     backbone (32 x 2 x 8 x T x 128, bf16): algorithmic bytes = read + write of the retained
@@ -277,6 +327,9 @@ def main():
     bwd = args.passes == "fwd+bwd"
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "summary":
+        print(json.dumps(summary_sweep(torch, B, W, args)))
         return
     if args.sweep == "kv":
         print(json.dumps(kv_sweep(torch, B, W, args)))

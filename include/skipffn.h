@@ -154,6 +154,40 @@ int skipffn_kv_compact(const void* src, void* dst, int64_t n_slabs, int64_t T, i
                        int64_t src_slab_bytes, int64_t dst_slab_bytes,
                        const int32_t* idx, int64_t R, const int32_t* num_retained, void* stream);
 
+/* ---- adaptive summary layer (Section 4.2, the summary-token equation) ------------------
+ *     x^s = softmax(X w^T)^T X
+ * X [n, C] a set of visual tokens, w [1, C] the layer's weight, the softmax taken over the
+ * n tokens: one summary row per token set.  A call handles S sets at once:
+ *   hidden  bf16 [T, C]          token features
+ *   tok     i32 [n_tok] device   token indices, the sets laid one after the other
+ *   seg     i32 [S + 1] device   set s is tok[seg[s] .. seg[s+1]); sizes need not be known
+ *                                on the host.  Entries of tok outside [0, T) and segment
+ *                                bounds outside [0, n_tok] are ignored, never dereferenced.
+ *   w       bf16 [C]
+ *   out     bf16 [S, C] OUT      the summary tokens (an empty set gives a zero row)
+ *   saved   NULL (inference) or skipffn_summary_saved_bytes(n_tok, S, C) bytes OUT:
+ *           scores f32 [n_tok], log-sum-exp f32 [S], x^s in f32 [S, C]
+ *   workspace: at least skipffn_summary_workspace_bytes(n_tok, S, C)
+ * Backward, for L with dL/dx^s = grad_out bf16 [S, C]:
+ *   grad_hidden bf16 [T, C] IN/OUT: row t of every listed token becomes
+ *       bf16(grad_hidden[t] + p_t * grad_out[s] + ds_t * w), ds_t = p_t (grad_out[s] . X_t -
+ *       grad_out[s] . x^s); rows not listed are not touched.  The sets must be disjoint.
+ *   dw  f32 [C] OUT: sum_t ds_t X_t over all sets, overwritten, or += with
+ *       SKIPFFN_FLAG_DW_ACCUMULATE (the only flag accepted); summed in a fixed order.
+ * C % 8 == 0; pointers 16-byte aligned (tok, seg: 4-byte).  S == 0 or n_tok == 0: only the
+ * zero rows / zero dw are written. */
+size_t skipffn_summary_saved_bytes(int64_t n_tok, int64_t S, int64_t C);
+size_t skipffn_summary_workspace_bytes(int64_t n_tok, int64_t S, int64_t C);
+int skipffn_summary_forward(int64_t T, int64_t C, const void* hidden,
+                            const int32_t* tok, const int32_t* seg, int64_t n_tok, int64_t S,
+                            const void* w, void* out, void* saved,
+                            void* workspace, size_t workspace_bytes, void* stream);
+int skipffn_summary_backward(int64_t T, int64_t C, const void* hidden,
+                             const int32_t* tok, const int32_t* seg, int64_t n_tok, int64_t S,
+                             const void* w, const void* saved, const void* grad_out,
+                             void* grad_hidden, void* dw,
+                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
+
 /* ---- layout of `saved`, for tests that compare stage by stage -------------
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];

@@ -392,6 +392,9 @@ def summary_forward(hidden_bits, tok, seg, w_bits):
     lse = np.zeros(S)
     for i in range(S):
         rows = tok[seg[i]:seg[i + 1]]
+        if len(rows) == 0:          # the paper does not define an empty set: zero row, lse = -inf
+            lse[i] = -np.inf
+            continue
         f = summary_forward_real(bf16_bits_to_f64(np.asarray(hidden_bits)[rows]), w)
         xs[i] = f["xs"]
         scores[seg[i]:seg[i + 1]] = f["s"]
@@ -411,6 +414,8 @@ def summary_backward(hidden_bits, tok, seg, w_bits, grad_out_bits, grad_hidden_b
     dw = np.zeros(hb.shape[1])
     for i in range(len(seg) - 1):
         rows = tok[seg[i]:seg[i + 1]]
+        if len(rows) == 0:
+            continue
         b = summary_backward_real(bf16_bits_to_f64(hb[rows]), w, bf16_bits_to_f64(np.asarray(grad_out_bits)[i]))
         gh_bits[rows] = f64_to_bf16_bits(bf16_bits_to_f64(gh_bits[rows]) + b["dX"])
         dw += b["dw"]

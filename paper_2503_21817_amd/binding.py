@@ -44,6 +44,13 @@ _SIGNATURES = {
                                     c_void_p, c_void_p]),
     "skipffn_kv_compact": (c_int, [c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int64, c_int64,
                                    c_void_p, c_int64, c_void_p, c_void_p]),
+    "skipffn_summary_saved_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
+    "skipffn_summary_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
+    "skipffn_summary_forward": (c_int, [c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_int64,
+                                        c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "skipffn_summary_backward": (c_int, [c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_int64,
+                                         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_size_t, c_uint32, c_void_p]),
     "skipffn_saved_layout": (c_int, [c_int64, c_int64, c_int64, POINTER(c_size_t)]),
     "skipffn_status_string": (c_char_p, [c_int]),
     "skipffn_last_hip_error": (c_int, []),
@@ -182,6 +189,37 @@ def skipffn_kv_compact(src, dst, idx, R, *, num_retained=None):
     _check(lib().skipffn_kv_compact(_ptr(src), _ptr(dst), n_slabs, T, row_bytes, T * row_bytes,
                                     dst.shape[-2] * row_bytes, _ptr(idx), Rv, nr, _stream()),
            "skipffn_kv_compact")
+
+
+def skipffn_summary_saved_bytes(n_tok, S, C) -> int:
+    return lib().skipffn_summary_saved_bytes(n_tok, S, C)
+
+
+def skipffn_summary_workspace_bytes(n_tok, S, C) -> int:
+    return lib().skipffn_summary_workspace_bytes(n_tok, S, C)
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def skipffn_summary_forward(hidden, tok, seg, w, out, *, saved=None, workspace=None):
+    """hidden bf16 [T, C]; tok i32 [n_tok]; seg i32 [S + 1]; w bf16 [C]; out bf16 [S, C]."""
+    T, C = hidden.shape
+    _check(lib().skipffn_summary_forward(T, C, _ptr(hidden), _ptr(tok), _ptr(seg), tok.numel(),
+                                         seg.numel() - 1, _ptr(w), _ptr(out), _ptr(saved),
+                                         _ptr(workspace), _nbytes(workspace), _stream()),
+           "skipffn_summary_forward")
+
+
+def skipffn_summary_backward(hidden, tok, seg, w, saved, grad_out, grad_hidden, dw, *, workspace=None,
+                             flags=0):
+    T, C = hidden.shape
+    _check(lib().skipffn_summary_backward(T, C, _ptr(hidden), _ptr(tok), _ptr(seg), tok.numel(),
+                                          seg.numel() - 1, _ptr(w), _ptr(saved), _ptr(grad_out),
+                                          _ptr(grad_hidden), _ptr(dw), _ptr(workspace),
+                                          _nbytes(workspace), flags, _stream()),
+           "skipffn_summary_backward")
 
 
 def skipffn_version() -> int:

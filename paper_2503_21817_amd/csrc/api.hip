@@ -142,7 +142,7 @@ const char* kernel_class_name(int kc) {
     static const char* names[KC_COUNT] = {
         "compact", "gather_rmsnorm", "gemm_gate_up_swiglu", "gemm_down", "resid_scatter",
         "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd+dw_down", "gemm_dw_gate_up",
-        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact"};
+        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact", "summary_fwd", "summary_bwd"};
     return (kc >= 0 && kc < KC_COUNT) ? names[kc] : "?";
 }
 
@@ -538,6 +538,106 @@ int skipffn_kv_compact(const void* src, void* dst, int64_t n_slabs, int64_t T, i
     if (a0 < b1 && b0 < a1) return SKIPFFN_EINVAL;
     hipError_t e = launch_kv_compact(src, dst, n_slabs, row_bytes, src_slab_bytes, dst_slab_bytes, idx,
                                      (int)Rb, R < 0 ? num_retained : nullptr, (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+// ---- adaptive summary layer ------------------------------------------------------------------
+namespace {
+struct SumSaved { size_t scores, lse, xs, total; };
+SumSaved sum_saved(int64_t n_tok, int64_t S, int64_t C) {
+    SumSaved L; size_t o = 0;
+    L.scores = o; o += align_up((size_t)n_tok * 4);
+    L.lse = o;    o += align_up((size_t)S * 4);
+    L.xs = o;     o += align_up((size_t)S * C * 4);
+    L.total = o;
+    return L;
+}
+struct SumWs { size_t acc, md, total; };
+SumWs sum_ws(int64_t n_tok, int64_t S, int64_t C) {
+    const size_t nq = (size_t)summary_max_chunks(n_tok, S);
+    SumWs W; size_t o = 0;
+    W.acc = o; o += align_up(nq * (size_t)C * 4);     // forward: weighted row sums; backward: dw
+    W.md = o;  o += align_up(nq * 2 * 4);
+    W.total = o;
+    return W;
+}
+int check_summary(int64_t T, int64_t C, int64_t n_tok, int64_t S) {
+    if (T < 0 || C <= 0 || n_tok < 0 || S < 0) return SKIPFFN_EINVAL;
+    if (C & 7) return SKIPFFN_ESHAPE;
+    if (T * C * 2 >= kMaxTensorBytes || T > 0x7fffffff || n_tok > 0x7fffffff || S > 65535 ||
+        summary_max_chunks(n_tok, S) * C * 4 >= ((int64_t)1 << 40))
+        return SKIPFFN_ESHAPE;
+    return SKIPFFN_OK;
+}
+}  // namespace
+
+size_t skipffn_summary_saved_bytes(int64_t n_tok, int64_t S, int64_t C) {
+    if (n_tok < 0 || S < 0 || C <= 0) return 0;
+    return sum_saved(n_tok, S, C).total + 256;
+}
+size_t skipffn_summary_workspace_bytes(int64_t n_tok, int64_t S, int64_t C) {
+    if (n_tok < 0 || S < 0 || C <= 0) return 0;
+    return sum_ws(n_tok, S, C).total + 256;
+}
+
+int skipffn_summary_forward(int64_t T, int64_t C, const void* hidden, const int32_t* tok,
+                            const int32_t* seg, int64_t n_tok, int64_t S, const void* w, void* out,
+                            void* saved, void* workspace, size_t workspace_bytes, void* stream) {
+    int st = check_summary(T, C, n_tok, S);
+    if (st != SKIPFFN_OK) return st;
+    if (S == 0) return SKIPFFN_OK;
+    if (bad_ptr(out) || bad_ptr(w) || seg == nullptr || (reinterpret_cast<uintptr_t>(seg) & 3u)) return SKIPFFN_EINVAL;
+    if (n_tok > 0 && (tok == nullptr || (reinterpret_cast<uintptr_t>(tok) & 3u))) return SKIPFFN_EINVAL;
+    if (T > 0 && bad_ptr(hidden)) return SKIPFFN_EINVAL;
+    if (saved != nullptr && !aligned16(saved)) return SKIPFFN_EINVAL;
+    const SumWs W = sum_ws(n_tok, S, C);
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
+    const SumSaved L = sum_saved(n_tok, S, C);
+    char* sv = static_cast<char*>(saved);
+    char* ws = static_cast<char*>(workspace);
+    hipError_t e = launch_summary_forward(
+        static_cast<const bf16_t*>(hidden), T, (int)C, tok, seg, n_tok, (int)S,
+        static_cast<const bf16_t*>(w), static_cast<bf16_t*>(out),
+        sv ? reinterpret_cast<float*>(sv + L.scores) : nullptr,
+        sv ? reinterpret_cast<float*>(sv + L.lse) : nullptr,
+        sv ? reinterpret_cast<float*>(sv + L.xs) : nullptr,
+        reinterpret_cast<float*>(ws + W.acc), reinterpret_cast<float*>(ws + W.md), (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+int skipffn_summary_backward(int64_t T, int64_t C, const void* hidden, const int32_t* tok,
+                             const int32_t* seg, int64_t n_tok, int64_t S, const void* w,
+                             const void* saved, const void* grad_out, void* grad_hidden, void* dw,
+                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
+    int st = check_summary(T, C, n_tok, S);
+    if (st != SKIPFFN_OK) return st;
+    if (flags & ~SKIPFFN_FLAG_DW_ACCUMULATE) return SKIPFFN_EUNSUPPORTED;
+    if (bad_ptr(dw)) return SKIPFFN_EINVAL;
+    const bool accum = (flags & SKIPFFN_FLAG_DW_ACCUMULATE) != 0;
+    hipStream_t s = (hipStream_t)stream;
+    if (S == 0) {
+        if (!accum) {
+            hipError_t e0 = launch_fill_zero(dw, (size_t)C * 4, s);
+            if (e0 != hipSuccess) return hip_fail(e0);
+        }
+        return SKIPFFN_OK;
+    }
+    if (bad_ptr(w) || bad_ptr(saved) || bad_ptr(grad_out) || seg == nullptr ||
+        (reinterpret_cast<uintptr_t>(seg) & 3u))
+        return SKIPFFN_EINVAL;
+    if (n_tok > 0 && (tok == nullptr || (reinterpret_cast<uintptr_t>(tok) & 3u))) return SKIPFFN_EINVAL;
+    if (T > 0 && (bad_ptr(hidden) || bad_ptr(grad_hidden))) return SKIPFFN_EINVAL;
+    const SumWs W = sum_ws(n_tok, S, C);
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
+    const SumSaved L = sum_saved(n_tok, S, C);
+    const char* sv = static_cast<const char*>(saved);
+    char* ws = static_cast<char*>(workspace);
+    hipError_t e = launch_summary_backward(
+        static_cast<const bf16_t*>(hidden), T, (int)C, tok, seg, n_tok, (int)S,
+        static_cast<const bf16_t*>(w), reinterpret_cast<const float*>(sv + L.xs),
+        reinterpret_cast<const float*>(sv + L.scores), reinterpret_cast<const float*>(sv + L.lse),
+        static_cast<const bf16_t*>(grad_out), static_cast<bf16_t*>(grad_hidden),
+        reinterpret_cast<float*>(ws + W.acc), static_cast<float*>(dw), accum ? 1 : 0, s);
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 

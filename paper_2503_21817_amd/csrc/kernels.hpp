@@ -25,6 +25,8 @@ enum KernelClass : int {
     KC_RMSNORM_BWD,
     KC_FILL,
     KC_KV_COMPACT,
+    KC_SUMMARY_FWD,
+    KC_SUMMARY_BWD,
     KC_COUNT
 };
 const char* kernel_class_name(int kc);
@@ -74,6 +76,19 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl
 // bytes of the gain-gradient scratch (one fp32 row of C per strip of rows)
 size_t gain_partial_bytes(int64_t R, int64_t C);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+// ---- adaptive summary layer -------------------------------------------------------------------
+constexpr int SUM_CH = 16;        // tokens per workgroup chunk
+int64_t summary_max_chunks(int64_t n_tok, int64_t S);      // chunks the launches cover
+hipError_t launch_summary_forward(const bf16_t* hidden, int64_t T, int C, const int32_t* tok,
+                                  const int32_t* seg, int64_t n_tok, int S, const bf16_t* w,
+                                  bf16_t* out, float* scores, float* lse, float* xs_f32,
+                                  float* part_acc, float* part_md, hipStream_t s);
+hipError_t launch_summary_backward(const bf16_t* hidden, int64_t T, int C, const int32_t* tok,
+                                   const int32_t* seg, int64_t n_tok, int S, const bf16_t* w,
+                                   const float* xs_f32, const float* scores, const float* lse,
+                                   const bf16_t* gout, bf16_t* grad_hidden, float* part_dw, float* dw,
+                                   int accumulate, hipStream_t s);
 
 // ---- GEMMs -----------------------------------------------------------------------
 hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation (once per process)

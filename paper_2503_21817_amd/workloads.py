@@ -147,3 +147,30 @@ def make_gain(w: Workload, unit: bool = True) -> np.ndarray:
         return _bf16_bits(np.ones(w.C, dtype=np.float32))
     rng = np.random.default_rng(w.seed + 30_000)
     return _bf16_bits(1.0 + 0.1 * rng.standard_normal(w.C, dtype=np.float32))
+
+
+def make_summary_sets(w: Workload):
+    """Token sets for the adaptive summary layer (Section 4.2): per sequence two disjoint
+    sets, the retained and then the skipped visual tokens (the paper puts one summary token
+    at each end of the skipped run).  Returns (tok int32 [n_tok], seg int32 [2 B + 1])."""
+    mask = make_mask(w)
+    tok, seg = [], [0]
+    base = 0
+    for v, t in zip(w.visual, w.text):
+        vis = np.arange(base, base + v)
+        m = mask[base:base + v]
+        for part in (vis[m == 0], vis[m != 0]):
+            tok.append(part)
+            seg.append(seg[-1] + len(part))
+        base += v + t
+    tok = np.concatenate(tok) if tok else np.zeros(0, np.int64)
+    return tok.astype(np.int32), np.asarray(seg, dtype=np.int32)
+
+
+def make_summary_weight(w: Workload) -> np.ndarray:
+    """Weight row of the summary layer, bf16 bits [C], ~ N(0, 0.02): scores X w have a
+    standard deviation of about 0.02 * sqrt(C), i.e. a softmax that is neither flat nor
+    one-hot at C = 4096."""
+    rng = np.random.default_rng(w.seed + 40_000)
+    return _bf16_bits(np.float32(0.02) * rng.standard_normal(w.C, dtype=np.float32))
+

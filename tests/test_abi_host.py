@@ -132,6 +132,27 @@ def test_compact_and_gather_reject_bad_arguments_on_the_host():
     assert kv(FAKE, FAR, 4, 10, 32, 320, 320, FAKE, 0, None, None) == B.OK          # nothing retained
 
 
+def test_summary_layer_rejects_bad_arguments_on_the_host():
+    lib = B.lib()
+    f, b = lib.skipffn_summary_forward, lib.skipffn_summary_backward
+    BIG = 1 << 40
+    # T, C, hidden, tok, seg, n_tok, S, w, out, saved, workspace, workspace_bytes, stream
+    assert f(10, 60, FAKE, FAKE, FAKE, 5, 1, FAKE, FAKE, None, FAKE, BIG, None) == B.ESHAPE
+    assert f(10, 64, FAKE, FAKE, FAKE, -1, 1, FAKE, FAKE, None, FAKE, BIG, None) == B.EINVAL
+    assert f(10, 64, FAKE, FAKE, None, 5, 1, FAKE, FAKE, None, FAKE, BIG, None) == B.EINVAL
+    assert f(10, 64, FAKE, None, FAKE, 5, 1, FAKE, FAKE, None, FAKE, BIG, None) == B.EINVAL
+    assert f(10, 64, FAKE, FAKE, FAKE, 5, 1, ODD, FAKE, None, FAKE, BIG, None) == B.EINVAL
+    assert f(10, 64, FAKE, FAKE, FAKE, 5, 1, FAKE, FAKE, None, FAKE, 16, None) == B.EWORKSPACE
+    assert f(10, 64, FAKE, FAKE, FAKE, 5, 0, FAKE, FAKE, None, FAKE, BIG, None) == B.OK      # no sets
+    assert lib.skipffn_summary_workspace_bytes(1000, 4, 4096) >= (1000 // 16 + 4) * 4096 * 4
+    assert lib.skipffn_summary_saved_bytes(1000, 4, 4096) >= 1000 * 4 + 4 * 4 + 4 * 4096 * 4
+    # ..., w, saved, grad_out, grad_hidden, dw, workspace, workspace_bytes, flags, stream
+    assert b(10, 64, FAKE, FAKE, FAKE, 5, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, 0x1, None) == B.EUNSUPPORTED
+    assert b(10, 64, FAKE, FAKE, FAKE, 5, 1, FAKE, FAKE, FAKE, FAKE, None, FAKE, BIG, 0, None) == B.EINVAL
+    assert b(10, 64, FAKE, FAKE, FAKE, 5, 1, FAKE, None, FAKE, FAKE, FAKE, FAKE, BIG, 0, None) == B.EINVAL
+    assert b(10, 64, FAKE, FAKE, FAKE, 5, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, 0, None) == B.EWORKSPACE
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

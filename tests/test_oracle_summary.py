@@ -108,3 +108,20 @@ def test_bf16_interface_segments():
         tot += O.summary_backward_real(O.bf16_bits_to_f64(hid[rows]), O.bf16_bits_to_f64(wb),
                                        O.bf16_bits_to_f64(gout[i]))["dw"]
     assert np.allclose(b["dw"], tot, rtol=1e-14)
+
+
+def test_empty_set_gives_a_zero_row_and_no_gradient():
+    rng = np.random.default_rng(8)
+    hid = O.f64_to_bf16_bits(rng.standard_normal((10, 8)))
+    wb = O.f64_to_bf16_bits(rng.standard_normal(8))
+    tok = np.array([1, 2, 5], dtype=np.int32)
+    seg = np.array([0, 2, 2, 3], dtype=np.int32)            # the middle set is empty
+    f = O.summary_forward(hid, tok, seg, wb)
+    assert np.all(f["out_bits"][1] == 0) and f["lse"][1] == -np.inf
+    gout = O.f64_to_bf16_bits(rng.standard_normal((3, 8)))
+    gh0 = O.f64_to_bf16_bits(rng.standard_normal((10, 8)))
+    with_empty = O.summary_backward(hid, tok, seg, wb, gout, gh0)
+    without = O.summary_backward(hid, tok, np.array([0, 2, 3], dtype=np.int32), wb, gout[[0, 2]], gh0)
+    assert np.array_equal(with_empty["gh_bits"], without["gh_bits"])
+    assert np.array_equal(with_empty["dw"], without["dw"])
+
