@@ -53,6 +53,9 @@ def parse():
                          "2, 3 and 5; summary: the adaptive summary layer, forward and backward, on "
                          "the visual token sets of the same mixes.  The JSON line then carries a 'sweep' array")
     ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays (the per-kernel events "
+                         "still come from eager launches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle leg")
     return ap.parse_args()
@@ -388,10 +391,30 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(args.warmup + i)
-    torch.cuda.synchronize()
+    if args.graph:
+        # one graph per input copy would be needed to rotate inputs; replaying on one copy lets
+        # values drift in place, which does not change the work done
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step(0)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step(0)
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_step = dt / args.steps * 1e3
 
@@ -447,7 +470,8 @@ def main():
         "dtype": "bf16", "data": data,
         "config": {"workload": f"{w.name}: T={T} tokens, R={R} retained, C={C}, I={I}, "
                                f"{L} layer{'s' if L > 1 else ''}, {args.passes}, in place",
-                   "T": T, "R": R, "C": C, "I": I, "layers": L, "passes": args.passes},
+                   "T": T, "R": R, "C": C, "I": I, "layers": L, "passes": args.passes,
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "gemm_only_tflops": round(flops / (gemm_ms * 1e-3) / 1e12, 2) if gemm_ms > 0 else None,
         "effective_tokens_per_s": round(T / (ms_step * 1e-3)),
