@@ -421,3 +421,51 @@ def summary_backward(hidden_bits, tok, seg, w_bits, grad_out_bits, grad_hidden_b
         dw += b["dw"]
     return {"gh_bits": gh_bits, "dw": dw}
 
+
+# --------------------------------------------------------------------------
+# Retained-token selection for a backbone without global / local views
+# (Section 4.1): the n visual tokens most similar to the CLS token are
+# retained, the rest are skipped.  Similarity = cosine similarity.
+# --------------------------------------------------------------------------
+
+def cls_similarity(features, cls):
+    """features float64 [n, Cv], cls float64 [Cv] -> cosine similarity [n]
+    (0 where a vector has zero length)."""
+    F = np.asarray(features, dtype=np.float64)
+    c = np.asarray(cls, dtype=np.float64)
+    num = F @ c
+    den = np.sqrt(np.sum(F * F, axis=1)) * np.sqrt(np.sum(c * c))
+    out = np.zeros(F.shape[0])
+    nz = den > 0
+    out[nz] = num[nz] / den[nz]
+    return out
+
+
+def select_top_n(sim, n_keep):
+    """sim [n] -> skip mask uint8 [n]: 0 for the n_keep tokens of highest similarity
+    (equal similarities: the lower index first), 1 for the rest."""
+    sim = np.asarray(sim)
+    n = sim.shape[0]
+    k = max(0, min(int(n_keep), n))
+    order = np.argsort(-sim, kind="stable")        # descending, ties by index
+    mask = np.ones(n, dtype=np.uint8)
+    mask[order[:k]] = 0
+    return mask
+
+
+def select_retained(features_bits, cls_bits, seq_off, n_keep):
+    """bf16 interface over B sequences: features uint16 [n_feat, Cv], cls uint16 [B, Cv],
+    seq_off [B + 1] (rows of sequence b: seq_off[b] .. seq_off[b+1]), n_keep int or [B].
+    Returns dict: mask uint8 [n_feat] (0 = retained) and sim float64 [n_feat]."""
+    seq_off = np.asarray(seq_off, dtype=np.int64)
+    B = len(seq_off) - 1
+    nk = np.broadcast_to(np.asarray(n_keep, dtype=np.int64), (B,))
+    fb = np.asarray(features_bits)
+    sim = np.zeros(fb.shape[0])
+    mask = np.ones(fb.shape[0], dtype=np.uint8)
+    for b in range(B):
+        lo, hi = seq_off[b], seq_off[b + 1]
+        sim[lo:hi] = cls_similarity(bf16_bits_to_f64(fb[lo:hi]), bf16_bits_to_f64(np.asarray(cls_bits)[b]))
+        mask[lo:hi] = select_top_n(sim[lo:hi], nk[b])
+    return {"mask": mask, "sim": sim}
+
