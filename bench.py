@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
@@ -270,6 +270,43 @@ def summary_sweep(torch, B, W, args):
             "sweep": rows}
 
 
+def select_sweep(torch, B, W, args):
+    """Retained-token selection (Section 4.1): cosine similarity of every visual token to its
+    sequence's CLS token, then the top-n rank count.  Vision width 1024 (the paper's ViT-L
+    class encoders); algorithmic bytes = one read of the features, n_feat * Cv * 2."""
+    rows = []
+    Cv = 1024
+    for cfg in (2, 3, 5):
+        w = W.config(cfg)
+        lens = list(w.visual)
+        n = sum(lens)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(700 + cfg)
+        feat = torch.randn((n, Cv), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        cls = torch.randn((len(lens), Cv), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+        keep = torch.from_numpy(np.asarray(w.keep, dtype=np.int32)).cuda()
+        mask = torch.empty(n, dtype=torch.uint8, device="cuda")
+        sim = torch.empty(n, dtype=torch.float32, device="cuda")
+        for _ in range(args.warmup):
+            B.skipffn_select_retained(feat, cls, off, keep, mask, sim)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.skipffn_select_retained(feat, cls, off, keep, mask, sim)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        assert int((mask == 0).sum().item()) == sum(w.keep)
+        gbs = n * Cv * 2 / (ms * 1e-3) / 1e9
+        rows.append({"workload": w.name, "n_feat": n, "sequences": len(lens), "us": round(ms * 1e3, 1),
+                     "gbs": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)})
+    return {"metric": "retained-token selection", "unit": "us", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "dtype": "bf16 in, f32 similarities", "data": "synthetic",
+            "config": {"workload": "visual tokens of configurations 2, 3, 5, vision width 1024"},
+            "sweep": rows}
+
+
 def kv_sweep(torch, B, W, args):
     """Skip KV-cache (Section 4.3) on a packed cache [layers, 2, kv heads, T, head dim] of the
     backbone (32 x 2 x 8 x T x 128, bf16): algorithmic bytes = read + write of the retained
@@ -330,6 +367,9 @@ def main():
     bwd = args.passes == "fwd+bwd"
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "select":
+        print(json.dumps(select_sweep(torch, B, W, args)))
         return
     if args.sweep == "summary":
         print(json.dumps(summary_sweep(torch, B, W, args)))

@@ -188,6 +188,28 @@ int skipffn_summary_backward(int64_t T, int64_t C, const void* hidden,
                              void* grad_hidden, void* dw,
                              void* workspace, size_t workspace_bytes, uint32_t flags, void* stream);
 
+/* ---- retained-token selection (Section 4.1) --------------------------------------------
+ * For a backbone without global / local views the paper retains, per sequence, the n visual
+ * tokens most similar to the CLS token and skips the rest.  Similarity is the cosine of the
+ * vision features; a token is retained iff fewer than n tokens of its sequence have a larger
+ * similarity (equal similarities: the lower index first), so the mask is unique for the
+ * float32 similarities computed, which are returned.
+ *   features  bf16 [n_feat, Cv]  visual tokens of all sequences, packed
+ *   cls       bf16 [B, Cv]       one CLS row per sequence
+ *   seq_off   i32 [B + 1] device rows of sequence b: seq_off[b] .. seq_off[b+1]) (clamped to n_feat)
+ *   n_keep / n_keep_dev          retained count n: one host value, or i32 [B] on the device
+ *   mask      u8 [n_feat] OUT    0 = retained, 1 = skipped, in feature order
+ *   sim       f32 [n_feat] OUT   the similarities (also the kernels' scratch: required)
+ *   token_pos, skip_mask, T      optional pair: token_pos i32 [n_feat] gives each visual token's
+ *       position in a flat token sequence of length T and skip_mask u8 [T] receives the same
+ *       value there (other entries, e.g. text tokens, are not touched; positions outside
+ *       [0, T) are ignored) - the mask skipffn_compact consumes, without a host round trip.
+ * Cv % 8 == 0; features, cls 16-byte aligned. */
+int skipffn_select_retained(const void* features, const void* cls, const int32_t* seq_off,
+                            int64_t n_feat, int64_t B, int64_t Cv, int64_t n_keep,
+                            const int32_t* n_keep_dev, uint8_t* mask, float* sim,
+                            const int32_t* token_pos, uint8_t* skip_mask, int64_t T, void* stream);
+
 /* ---- layout of `saved`, for tests that compare stage by stage -------------
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];

@@ -51,6 +51,8 @@ _SIGNATURES = {
     "skipffn_summary_backward": (c_int, [c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_int64,
                                          c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
                                          c_size_t, c_uint32, c_void_p]),
+    "skipffn_select_retained": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int64,
+                                        c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]),
     "skipffn_saved_layout": (c_int, [c_int64, c_int64, c_int64, POINTER(c_size_t)]),
     "skipffn_status_string": (c_char_p, [c_int]),
     "skipffn_last_hip_error": (c_int, []),
@@ -220,6 +222,21 @@ def skipffn_summary_backward(hidden, tok, seg, w, saved, grad_out, grad_hidden, 
                                           _ptr(grad_hidden), _ptr(dw), _ptr(workspace),
                                           _nbytes(workspace), flags, _stream()),
            "skipffn_summary_backward")
+
+
+def skipffn_select_retained(features, cls, seq_off, n_keep, mask, sim, *, token_pos=None, skip_mask=None):
+    """features bf16 [n_feat, Cv]; cls bf16 [B, Cv]; seq_off i32 [B + 1]; n_keep: int, or an
+    i32 [B] device tensor; mask u8 [n_feat]; sim f32 [n_feat]."""
+    n_feat, Cv = features.shape
+    nb = seq_off.numel() - 1
+    if isinstance(n_keep, torch.Tensor):
+        nk, nkd = 0, _ptr(n_keep)
+    else:
+        nk, nkd = int(n_keep), None
+    T = 0 if skip_mask is None else skip_mask.numel()
+    _check(lib().skipffn_select_retained(_ptr(features), _ptr(cls), _ptr(seq_off), n_feat, nb, Cv, nk, nkd,
+                                         _ptr(mask), _ptr(sim), _ptr(token_pos), _ptr(skip_mask), T,
+                                         _stream()), "skipffn_select_retained")
 
 
 def skipffn_version() -> int:

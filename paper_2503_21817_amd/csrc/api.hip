@@ -142,7 +142,7 @@ const char* kernel_class_name(int kc) {
     static const char* names[KC_COUNT] = {
         "compact", "gather_rmsnorm", "gemm_gate_up_swiglu", "gemm_down", "resid_scatter",
         "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd+dw_down", "gemm_dw_gate_up",
-        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact", "summary_fwd", "summary_bwd"};
+        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact", "summary_fwd", "summary_bwd", "select_retained"};
     return (kc >= 0 && kc < KC_COUNT) ? names[kc] : "?";
 }
 
@@ -638,6 +638,27 @@ int skipffn_summary_backward(int64_t T, int64_t C, const void* hidden, const int
         reinterpret_cast<const float*>(sv + L.scores), reinterpret_cast<const float*>(sv + L.lse),
         static_cast<const bf16_t*>(grad_out), static_cast<bf16_t*>(grad_hidden),
         reinterpret_cast<float*>(ws + W.acc), static_cast<float*>(dw), accum ? 1 : 0, s);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+// ---- retained-token selection --------------------------------------------------------------------
+int skipffn_select_retained(const void* features, const void* cls, const int32_t* seq_off,
+                            int64_t n_feat, int64_t B, int64_t Cv, int64_t n_keep,
+                            const int32_t* n_keep_dev, uint8_t* mask, float* sim,
+                            const int32_t* token_pos, uint8_t* skip_mask, int64_t T, void* stream) {
+    if (n_feat < 0 || B < 0 || Cv <= 0 || n_keep < 0 || T < 0) return SKIPFFN_EINVAL;
+    if (Cv & 7) return SKIPFFN_ESHAPE;
+    if (n_feat > 0x7fffffff || B > 65535 || n_keep > 0x7fffffff || T > 0x7fffffff ||
+        n_feat * Cv * 2 >= kMaxTensorBytes)
+        return SKIPFFN_ESHAPE;
+    if (B == 0 || n_feat == 0) return SKIPFFN_OK;
+    if (bad_ptr(features) || bad_ptr(cls) || seq_off == nullptr || mask == nullptr || sim == nullptr)
+        return SKIPFFN_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(seq_off) & 3u) || (reinterpret_cast<uintptr_t>(sim) & 3u)) return SKIPFFN_EINVAL;
+    if ((token_pos == nullptr) != (skip_mask == nullptr)) return SKIPFFN_EINVAL;
+    hipError_t e = launch_select_retained(static_cast<const bf16_t*>(features), static_cast<const bf16_t*>(cls),
+                                          seq_off, n_feat, (int)B, (int)Cv, (int)n_keep, n_keep_dev, mask,
+                                          sim, token_pos, skip_mask, T, (hipStream_t)stream);
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 

@@ -27,6 +27,7 @@ enum KernelClass : int {
     KC_KV_COMPACT,
     KC_SUMMARY_FWD,
     KC_SUMMARY_BWD,
+    KC_SELECT,
     KC_COUNT
 };
 const char* kernel_class_name(int kc);
@@ -89,6 +90,13 @@ hipError_t launch_summary_backward(const bf16_t* hidden, int64_t T, int C, const
                                    const float* xs_f32, const float* scores, const float* lse,
                                    const bf16_t* gout, bf16_t* grad_hidden, float* part_dw, float* dw,
                                    int accumulate, hipStream_t s);
+
+// ---- retained-token selection ---------------------------------------------------------------------
+constexpr int SEL_CH = 16;        // tokens per workgroup of the similarity kernel
+hipError_t launch_select_retained(const bf16_t* feat, const bf16_t* cls, const int32_t* seq_off,
+                                  int64_t n_feat, int B, int Cv, int n_keep, const int32_t* n_keep_dev,
+                                  uint8_t* mask, float* sim, const int32_t* token_pos,
+                                  uint8_t* skip_mask, int64_t T, hipStream_t s);
 
 // ---- GEMMs -----------------------------------------------------------------------
 hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation (once per process)

@@ -10,69 +10,13 @@
 // small kernel merges the chunks of a set.  The launch covers the upper bound
 // ceil(n_tok / SUM_CH) + S chunks; workgroups past the real count exit.
 #include "kernels.hpp"
+#include "segments.hpp"
 
 namespace skipffn {
 
 constexpr int SUM_THREADS = 256;
 static_assert(SUM_CH == 16, "four wavefronts of four tokens");
 constexpr float kNoScore = -3.0e38f;      // score of an out-of-range token index: weight 0
-
-__device__ __forceinline__ void unpack8s(const u32x4& v, float* f) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        f[2 * j] = bf16lo_to_f32(v[j]);
-        f[2 * j + 1] = bf16hi_to_f32(v[j]);
-    }
-}
-
-// token positions [b, e) of set i, clamped to the token list so that a malformed seg array
-// cannot send a read outside tok
-__device__ __forceinline__ void seg_bounds(const int32_t* __restrict__ seg, int i, int n_tok, int& b, int& e) {
-    e = seg[i + 1];
-    e = e < 0 ? 0 : (e > n_tok ? n_tok : e);
-    b = seg[i];
-    b = b < 0 ? 0 : (b > e ? e : b);
-}
-// chunk q -> (set s, first token position t0, token count nt); false past the last chunk
-__device__ __forceinline__ bool locate_chunk(const int32_t* __restrict__ seg, int S, int n_tok, int q,
-                                             int& s, int& t0, int& nt) {
-    int cc = 0;
-    for (int i = 0; i < S; ++i) {
-        int b, e;
-        seg_bounds(seg, i, n_tok, b, e);
-        const int nc = (e - b + SUM_CH - 1) / SUM_CH;
-        if (q < cc + nc) {
-            s = i;
-            t0 = b + (q - cc) * SUM_CH;
-            nt = e - t0 < SUM_CH ? e - t0 : SUM_CH;
-            return true;
-        }
-        cc += nc;
-    }
-    return false;
-}
-// chunks [q0, q1) of set s, clamped to the nq_max chunks the launch covers
-__device__ __forceinline__ void chunk_range(const int32_t* __restrict__ seg, int s, int n_tok, int nq_max,
-                                            int& q0, int& q1) {
-    int cc = 0;
-    for (int i = 0; i < s; ++i) {
-        int b, e;
-        seg_bounds(seg, i, n_tok, b, e);
-        cc += (e - b + SUM_CH - 1) / SUM_CH;
-    }
-    int b, e;
-    seg_bounds(seg, s, n_tok, b, e);
-    q0 = cc < nq_max ? cc : nq_max;
-    q1 = cc + (e - b + SUM_CH - 1) / SUM_CH;
-    q1 = q1 < nq_max ? q1 : nq_max;
-}
-
-__device__ __forceinline__ float block_sum256(float v, float* red) {
-    v = wave_sum(v);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    return (red[0] + red[1]) + (red[2] + red[3]);
-}
 
 // dots of up to four rows of `hidden` (row index < 0: skipped, result 0) with the row `b`, by
 // one wavefront; the four rows are loaded together so that their latencies overlap
@@ -109,7 +53,7 @@ __global__ __launch_bounds__(SUM_THREADS) void summary_chunk_fwd_kernel(
     __shared__ float sc[SUM_CH];
     __shared__ int rowid[SUM_CH];
     int s, t0, nt;
-    if (!locate_chunk(seg, S, n_tok, (int)blockIdx.x, s, t0, nt)) return;   // uniform over the workgroup
+    if (!locate_chunk<SUM_CH>(seg, S, n_tok, (int)blockIdx.x, s, t0, nt)) return;   // uniform over the workgroup
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int chunks = C >> 3;
     // phase A: scores s_t = X_t . w, four tokens per wavefront (SUM_CH = 16 = 4 waves x 4)
@@ -189,7 +133,7 @@ __global__ __launch_bounds__(SUM_THREADS) void summary_merge_fwd_kernel(
     const int s = blockIdx.x;
     const int tid = threadIdx.x;
     int q0, q1;
-    chunk_range(seg, s, n_tok, nq_max, q0, q1);
+    chunk_range<SUM_CH>(seg, s, n_tok, nq_max, q0, q1);
     // global maximum and denominator of the set
     float M = kNoScore;
     for (int q = q0 + tid; q < q1; q += SUM_THREADS) M = fmaxf(M, part_md[2 * q]);
@@ -259,7 +203,7 @@ __global__ __launch_bounds__(SUM_THREADS) void summary_chunk_bwd_kernel(
     __shared__ int rowid[SUM_CH];
     __shared__ float red[4];
     int s, t0, nt;
-    if (!locate_chunk(seg, S, n_tok, (int)blockIdx.x, s, t0, nt)) return;
+    if (!locate_chunk<SUM_CH>(seg, S, n_tok, (int)blockIdx.x, s, t0, nt)) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int chunks = C >> 3;
     const bf16_t* g = gout + (int64_t)s * C;
@@ -357,7 +301,7 @@ __global__ __launch_bounds__(SUM_THREADS) void summary_dw_reduce_kernel(
     int C, float* __restrict__ dw, int accumulate) {
     __shared__ float part4[4][64];
     int q0, q1;
-    chunk_range(seg, S - 1, n_tok, nq_max, q0, q1);           // q1 = total number of chunks
+    chunk_range<SUM_CH>(seg, S - 1, n_tok, nq_max, q0, q1);           // q1 = total number of chunks
     const int cx = threadIdx.x & 63, sy = threadIdx.x >> 6;
     const int c = blockIdx.x * 64 + cx;
     float acc = 0.0f;

@@ -153,6 +153,19 @@ def test_summary_layer_rejects_bad_arguments_on_the_host():
     assert b(10, 64, FAKE, FAKE, FAKE, 5, 1, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, 0, None) == B.EWORKSPACE
 
 
+def test_select_retained_rejects_bad_arguments_on_the_host():
+    f = B.lib().skipffn_select_retained
+    # features, cls, seq_off, n_feat, B, Cv, n_keep, n_keep_dev, mask, sim, token_pos, skip_mask, T, stream
+    assert f(FAKE, FAKE, FAKE, 10, 1, 60, 3, None, FAKE, FAKE, None, None, 0, None) == B.ESHAPE
+    assert f(FAKE, FAKE, FAKE, -1, 1, 64, 3, None, FAKE, FAKE, None, None, 0, None) == B.EINVAL
+    assert f(FAKE, FAKE, None, 10, 1, 64, 3, None, FAKE, FAKE, None, None, 0, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, 10, 1, 64, 3, None, None, FAKE, None, None, 0, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, 10, 1, 64, 3, None, FAKE, None, None, None, 0, None) == B.EINVAL
+    assert f(ODD, FAKE, FAKE, 10, 1, 64, 3, None, FAKE, FAKE, None, None, 0, None) == B.EINVAL
+    assert f(FAKE, FAKE, FAKE, 10, 1, 64, 3, None, FAKE, FAKE, FAKE, None, 5, None) == B.EINVAL   # half a pair
+    assert f(FAKE, FAKE, FAKE, 10, 0, 64, 3, None, FAKE, FAKE, None, None, 0, None) == B.OK       # no sequences
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
