@@ -469,3 +469,98 @@ def select_retained(features_bits, cls_bits, seq_off, n_keep):
         mask[lo:hi] = select_top_n(sim[lo:hi], nk[b])
     return {"mask": mask, "sim": sim}
 
+
+# --------------------------------------------------------------------------
+# Token merge of the skipped (local) visual tokens (Section 4.1, the three
+# bullet points): pairwise cosine similarities and their per-token average;
+# the k tokens of lowest average similarity are kept; every other token is
+# merged with the most similar kept token.  The paper does not spell out the
+# merge: here (as in the token-merging work it cites) a kept token becomes the
+# plain mean of itself and the tokens merged into it.
+# --------------------------------------------------------------------------
+
+def cosine_matrix(X):
+    """X float64 [n, C] -> [n, n] cosine similarities (a zero row has similarity 0 to
+    everything, itself included)."""
+    X = np.asarray(X, dtype=np.float64)
+    norm = np.sqrt(np.sum(X * X, axis=1))
+    Xn = np.zeros_like(X)
+    nz = norm > 0
+    Xn[nz] = X[nz] / norm[nz, None]
+    return Xn @ Xn.T
+
+
+def average_similarity(S):
+    """Mean similarity of every token to the OTHER tokens of its set (0 for a single token)."""
+    S = np.asarray(S, dtype=np.float64)
+    n = S.shape[0]
+    if n <= 1:
+        return np.zeros(n)
+    return (np.sum(S, axis=1) - np.diag(S)) / (n - 1)
+
+
+def merge_decisions(S, avg, k):
+    """-> (kept, assign): kept = ascending indices of the min(k, n) tokens of lowest average
+    similarity (equal averages: the lower index first); assign[i] = slot (position in kept)
+    of the kept token that token i ends up in: its own slot if kept, else the kept token of
+    highest similarity to it (equal similarities: the lower index)."""
+    S = np.asarray(S)
+    n = S.shape[0]
+    kk = max(0, min(int(k), n))
+    order = np.argsort(np.asarray(avg), kind="stable")          # ascending, ties by index
+    kept = np.sort(order[:kk])
+    slot_of = -np.ones(n, dtype=np.int64)
+    slot_of[kept] = np.arange(kk)
+    assign = slot_of.copy()
+    if kk > 0:
+        for i in range(n):
+            if slot_of[i] < 0:
+                assign[i] = int(np.argmax(S[i, kept]))          # first maximum = lowest index
+    return kept, assign
+
+
+def merge_rows(X, assign, kk):
+    """Plain mean of the rows assigned to every slot, rows added in index order."""
+    X = np.asarray(X, dtype=np.float64)
+    out = np.zeros((kk, X.shape[1]))
+    cnt = np.zeros(kk)
+    for i in range(X.shape[0]):
+        if assign[i] >= 0:
+            out[assign[i]] += X[i]
+            cnt[assign[i]] += 1
+    return out / np.maximum(cnt, 1)[:, None]
+
+
+def token_merge_real(X, k):
+    X = np.asarray(X, dtype=np.float64)
+    S = cosine_matrix(X)
+    avg = average_similarity(S)
+    kept, assign = merge_decisions(S, avg, k)
+    return {"merged": merge_rows(X, assign, len(kept)), "kept": kept, "assign": assign,
+            "S": S, "avg": avg}
+
+
+def token_merge(x_bits, seg, k):
+    """bf16 interface over several sets (set s = rows seg[s]:seg[s+1] of x_bits [n_tok, C]):
+    out_bits uint16 [S, k, C] (rows past a set's kept count are zero), kept int64 [S, k] (row
+    index in x_bits, -1 padding), assign int64 [n_tok] (slot), avg float64 [n_tok]."""
+    xb = np.asarray(x_bits)
+    seg = np.asarray(seg, dtype=np.int64)
+    S_sets = len(seg) - 1
+    C = xb.shape[1]
+    out = np.zeros((S_sets, k, C))
+    kept = -np.ones((S_sets, k), dtype=np.int64)
+    assign = -np.ones(xb.shape[0], dtype=np.int64)
+    avg = np.zeros(xb.shape[0])
+    for s in range(S_sets):
+        lo, hi = seg[s], seg[s + 1]
+        if hi <= lo:
+            continue
+        r = token_merge_real(bf16_bits_to_f64(xb[lo:hi]), k)
+        kk = len(r["kept"])
+        out[s, :kk] = r["merged"]
+        kept[s, :kk] = r["kept"] + lo
+        assign[lo:hi] = r["assign"]
+        avg[lo:hi] = r["avg"]
+    return {"out_bits": f64_to_bf16_bits(out), "merged": out, "kept": kept, "assign": assign, "avg": avg}
+

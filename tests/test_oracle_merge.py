@@ -1,0 +1,105 @@
+"""Pins for the oracle's token merge (Section 4.1): library cosine similarities, plain loops,
+closed forms and structural invariants."""
+import numpy as np
+import pytest
+from sklearn.metrics.pairwise import cosine_similarity
+
+from oracle import skipffn_oracle as O
+
+
+def test_cosine_matrix_against_the_library_and_a_loop():
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((13, 7))
+    S = O.cosine_matrix(X)
+    assert np.allclose(S, cosine_similarity(X), rtol=1e-13, atol=1e-15)
+    for i in range(13):
+        for j in range(13):
+            want = float(X[i] @ X[j]) / (np.linalg.norm(X[i]) * np.linalg.norm(X[j]))
+            assert abs(S[i, j] - want) < 1e-14
+    assert np.allclose(np.diag(S), 1.0) and np.allclose(S, S.T)
+    Z = X.copy(); Z[4] = 0
+    assert np.all(O.cosine_matrix(Z)[4] == 0)
+
+
+def test_average_excludes_the_token_itself():
+    S = np.array([[1.0, 0.5, -0.5], [0.5, 1.0, 0.0], [-0.5, 0.0, 1.0]])
+    assert np.allclose(O.average_similarity(S), [0.0, 0.25, -0.25])
+    assert np.all(O.average_similarity(np.ones((1, 1))) == 0)
+
+
+def brute(X, k):
+    """The three steps written as plain loops."""
+    n = len(X)
+    S = [[float(X[i] @ X[j]) / (np.linalg.norm(X[i]) * np.linalg.norm(X[j])) for j in range(n)] for i in range(n)]
+    avg = [sum(S[i][j] for j in range(n) if j != i) / (n - 1) for i in range(n)]
+    kept = []
+    for t in range(n):
+        lower = sum(1 for u in range(n) if avg[u] < avg[t] or (avg[u] == avg[t] and u < t))
+        if lower < k:
+            kept.append(t)
+    groups = {j: [j] for j in kept}
+    for i in range(n):
+        if i not in groups:
+            best = max(kept, key=lambda j: (S[i][j], -j))
+            groups[best].append(i)
+    merged = np.stack([np.mean([X[i] for i in sorted(groups[j])], axis=0) for j in kept])
+    return kept, groups, merged
+
+
+@pytest.mark.parametrize("n,k,seed", [(12, 4, 1), (9, 1, 2), (9, 9, 3), (30, 7, 4)])
+def test_against_plain_loops(n, k, seed):
+    X = np.random.default_rng(seed).standard_normal((n, 6))
+    r = O.token_merge_real(X, k)
+    kept, groups, merged = brute(X, k)
+    assert r["kept"].tolist() == kept
+    for slot, j in enumerate(kept):
+        assert sorted(np.flatnonzero(r["assign"] == slot).tolist()) == sorted(groups[j])
+    assert np.allclose(r["merged"], merged, rtol=1e-13, atol=1e-15)
+
+
+def test_closed_forms():
+    rng = np.random.default_rng(5)
+    X = rng.standard_normal((8, 5))
+    # k = n: nothing is merged;  k = 1: one token, the mean of all
+    assert np.array_equal(O.token_merge_real(X, 8)["merged"], X)
+    assert np.allclose(O.token_merge_real(X, 1)["merged"][0], X.mean(axis=0))
+    assert np.array_equal(O.token_merge_real(X, 20)["merged"], X)          # k > n
+    # a tight cluster plus one outlier orthogonal to it: the outlier has the lowest average
+    # similarity, so it is kept first; with k = 2 the cluster collapses onto its own kept member
+    a, b = np.array([1.0, 0, 0, 0, 0]), np.array([0, 1.0, 0, 0, 0])
+    Y = np.stack([a + 0.01 * rng.standard_normal(5) for _ in range(3)] + [b] +
+                 [a + 0.01 * rng.standard_normal(5) for _ in range(2)])
+    assert O.token_merge_real(Y, 1)["kept"].tolist() == [3]
+    r = O.token_merge_real(Y, 2)
+    assert 3 in r["kept"].tolist()
+    slot_out = r["kept"].tolist().index(3)
+    assert np.flatnonzero(r["assign"] == slot_out).tolist() == [3]          # nobody merges into the outlier
+    assert np.allclose(r["merged"][1 - slot_out], Y[[0, 1, 2, 4, 5]].mean(axis=0))
+    # a duplicated token goes to its twin (similarity exactly 1) when only the twin is kept
+    D = np.stack([X[0], X[1], X[2], X[1]])
+    S = O.cosine_matrix(D)
+    kept, assign = O.merge_decisions(S, np.array([0.0, 0.1, 0.2, 0.3]), 3)   # keep 0, 1, 2
+    assert kept.tolist() == [0, 1, 2] and assign.tolist() == [0, 1, 2, 1]
+
+
+def test_structure_every_token_lands_in_exactly_one_kept_slot():
+    X = np.random.default_rng(6).standard_normal((40, 8))
+    r = O.token_merge_real(X, 11)
+    assert len(r["kept"]) == 11 and np.all(np.diff(r["kept"]) > 0)
+    assert np.all((r["assign"] >= 0) & (r["assign"] < 11))
+    assert np.all(r["assign"][r["kept"]] == np.arange(11))
+    # the merge preserves the token sum weighted by group size
+    cnt = np.bincount(r["assign"], minlength=11)
+    assert np.allclose((r["merged"] * cnt[:, None]).sum(axis=0), X.sum(axis=0), rtol=1e-12)
+    # the kept tokens are the least similar on average
+    assert r["avg"][r["kept"]].max() <= np.delete(r["avg"], r["kept"]).min()
+
+
+def test_bf16_interface():
+    rng = np.random.default_rng(7)
+    xb = O.f64_to_bf16_bits(rng.standard_normal((25, 8)))
+    r = O.token_merge(xb, [0, 10, 10, 25], 6)
+    assert r["out_bits"].shape == (3, 6, 8) and np.all(r["out_bits"][1] == 0) and np.all(r["kept"][1] == -1)
+    one = O.token_merge_real(O.bf16_bits_to_f64(xb[10:25]), 6)
+    assert np.array_equal(r["kept"][2], one["kept"] + 10)
+    assert np.array_equal(r["out_bits"][2], O.f64_to_bf16_bits(one["merged"]))
