@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
@@ -307,6 +307,40 @@ def select_sweep(torch, B, W, args):
             "sweep": rows}
 
 
+def merge_sweep(torch, B, args):
+    """Token merge (Section 4.1): sets of 1024 local tokens reduced to 256 (the paper's ablation
+    setting), 8 and 32 sets, vision width 1024 and backbone width 4096.  The similarity GEMMs
+    are 2 * n^2 * C FLOP per set; the rest is memory-bound."""
+    rows = []
+    n, k = 1024, 256
+    for S, C in ((8, 1024), (32, 1024), (8, 4096)):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(800 + S + C)
+        x = torch.randn((S * n, C), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        seg = [i * n for i in range(S + 1)]
+        out = torch.empty((S, k, C), dtype=torch.bfloat16, device="cuda")
+        kept = torch.empty((S, k), dtype=torch.int32, device="cuda")
+        assign = torch.empty(S * n, dtype=torch.int32, device="cuda")
+        avg = torch.empty(S * n, dtype=torch.float32, device="cuda")
+        ws = torch.empty(B.skipffn_token_merge_workspace_bytes(S * n, n, C), dtype=torch.uint8, device="cuda")
+        for _ in range(args.warmup):
+            B.skipffn_token_merge(x, seg, k, out, kept, assign, avg, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.skipffn_token_merge(x, seg, k, out, kept, assign, avg, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        assert int((kept >= 0).sum().item()) == S * k
+        rows.append({"sets": S, "tokens_per_set": n, "kept": k, "C": C, "us": round(ms * 1e3, 1),
+                     "us_per_set": round(ms * 1e3 / S, 1),
+                     "similarity_gemm_gflop": round(2 * n * n * C * S / 1e9, 1)})
+    return {"metric": "token merge", "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "dtype": "bf16 in, f32 similarities", "data": "synthetic",
+            "config": {"workload": "1024 -> 256 tokens per set"}, "sweep": rows}
+
+
 def kv_sweep(torch, B, W, args):
     """Skip KV-cache (Section 4.3) on a packed cache [layers, 2, kv heads, T, head dim] of the
     backbone (32 x 2 x 8 x T x 128, bf16): algorithmic bytes = read + write of the retained
@@ -367,6 +401,9 @@ def main():
     bwd = args.passes == "fwd+bwd"
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "merge":
+        print(json.dumps(merge_sweep(torch, B, args)))
         return
     if args.sweep == "select":
         print(json.dumps(select_sweep(torch, B, W, args)))

@@ -210,6 +210,29 @@ int skipffn_select_retained(const void* features, const void* cls, const int32_t
                             const int32_t* n_keep_dev, uint8_t* mask, float* sim,
                             const int32_t* token_pos, uint8_t* skip_mask, int64_t T, void* stream);
 
+/* ---- token merge (Section 4.1, the three steps) ----------------------------------------
+ * Reduces each set of (local, skipped) visual tokens to k tokens: pairwise cosine
+ * similarities and their average per token (over the other tokens of the set); the k tokens
+ * of lowest average similarity are kept; every other token is merged into the kept token it
+ * is most similar to.  A kept token becomes the plain mean of itself and the tokens merged
+ * into it (the paper leaves the merge itself open).  Equal averages / similarities go to the
+ * lower index; decisions are taken on the float32 values computed, which are returned.
+ *   x         bf16 [n_tok, C]     tokens of all sets, set s = rows seg_host[s] .. seg_host[s+1])
+ *   seg_host  i32 [S + 1] HOST    ascending, seg_host[0] >= 0; at most 4096 rows per set
+ *   k                             tokens kept per set (<= 4096); a set of n <= k rows is kept whole
+ *   out       bf16 [S, k, C] OUT  merged tokens in the index order of the kept tokens; rows past
+ *                                 a set's kept count are zero
+ *   kept_idx  i32 [S, k] OUT      row index (in x) of every kept token, -1 padding
+ *   assign    i32 [n_tok] OUT     slot (0 .. k-1 within its set) each token ends up in
+ *   avg_sim   f32 [n_tok] OUT     the average similarities
+ *   workspace: at least skipffn_token_merge_workspace_bytes(n_tok, n_max, C), n_max = rows of
+ *              the largest set
+ * Forward only.  Sets are processed one after the other on the stream. */
+size_t skipffn_token_merge_workspace_bytes(int64_t n_tok, int64_t n_max, int64_t C);
+int skipffn_token_merge(const void* x, const int32_t* seg_host, int64_t S, int64_t C, int64_t k,
+                        void* out, int32_t* kept_idx, int32_t* assign, float* avg_sim,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- layout of `saved`, for tests that compare stage by stage -------------
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];

@@ -53,6 +53,9 @@ _SIGNATURES = {
                                          c_size_t, c_uint32, c_void_p]),
     "skipffn_select_retained": (c_int, [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int64,
                                         c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]),
+    "skipffn_token_merge_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
+    "skipffn_token_merge": (c_int, [c_void_p, POINTER(c_int32), c_int64, c_int64, c_int64, c_void_p, c_void_p,
+                                    c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
     "skipffn_saved_layout": (c_int, [c_int64, c_int64, c_int64, POINTER(c_size_t)]),
     "skipffn_status_string": (c_char_p, [c_int]),
     "skipffn_last_hip_error": (c_int, []),
@@ -237,6 +240,20 @@ def skipffn_select_retained(features, cls, seq_off, n_keep, mask, sim, *, token_
     _check(lib().skipffn_select_retained(_ptr(features), _ptr(cls), _ptr(seq_off), n_feat, nb, Cv, nk, nkd,
                                          _ptr(mask), _ptr(sim), _ptr(token_pos), _ptr(skip_mask), T,
                                          _stream()), "skipffn_select_retained")
+
+
+def skipffn_token_merge_workspace_bytes(n_tok, n_max, C) -> int:
+    return lib().skipffn_token_merge_workspace_bytes(n_tok, n_max, C)
+
+
+def skipffn_token_merge(x, seg, k, out, kept_idx, assign, avg_sim, *, workspace=None):
+    """x bf16 [n_tok, C]; seg: host sequence of S + 1 offsets; out bf16 [S, k, C];
+    kept_idx i32 [S, k]; assign i32 [n_tok]; avg_sim f32 [n_tok]."""
+    seg = [int(v) for v in seg]
+    arr = (c_int32 * len(seg))(*seg)
+    _check(lib().skipffn_token_merge(_ptr(x), arr, len(seg) - 1, x.shape[1], int(k), _ptr(out),
+                                     _ptr(kept_idx), _ptr(assign), _ptr(avg_sim), _ptr(workspace),
+                                     _nbytes(workspace), _stream()), "skipffn_token_merge")
 
 
 def skipffn_version() -> int:

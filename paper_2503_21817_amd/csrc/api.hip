@@ -5,6 +5,8 @@
 #include <vector>
 
 #include "../../include/skipffn.h"
+#include <algorithm>
+
 #include "kernels.hpp"
 
 using namespace skipffn;
@@ -142,7 +144,7 @@ const char* kernel_class_name(int kc) {
     static const char* names[KC_COUNT] = {
         "compact", "gather_rmsnorm", "gemm_gate_up_swiglu", "gemm_down", "resid_scatter",
         "passthrough_copy", "gather_rows", "gemm_dh_swiglu_bwd+dw_down", "gemm_dw_gate_up",
-        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact", "summary_fwd", "summary_bwd", "select_retained"};
+        "gemm_dxn", "rmsnorm_bwd_scatter", "fill_zero", "kv_compact", "summary_fwd", "summary_bwd", "select_retained", "token_merge"};
     return (kc >= 0 && kc < KC_COUNT) ? names[kc] : "?";
 }
 
@@ -659,6 +661,85 @@ int skipffn_select_retained(const void* features, const void* cls, const int32_t
     hipError_t e = launch_select_retained(static_cast<const bf16_t*>(features), static_cast<const bf16_t*>(cls),
                                           seq_off, n_feat, (int)B, (int)Cv, (int)n_keep, n_keep_dev, mask,
                                           sim, token_pos, skip_mask, T, (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+// ---- token merge -----------------------------------------------------------------------------------
+namespace {
+// sets handled per launch group: bounded by the kernel-argument table and by the size of the
+// similarity buffer (256 MB)
+int merge_group_sets(int64_t n_max) {
+    const int64_t ld = (n_max + 7) / 8 * 8;
+    const int64_t per_set = std::max<int64_t>(n_max * ld * 4, 1);
+    int64_t g = ((int64_t)256 << 20) / per_set;
+    g = std::max<int64_t>(1, std::min<int64_t>(g, SEG_TABLE_MAX));
+    return (int)g;
+}
+struct MergeWs { size_t xn, sim, slot, kept, total; };
+MergeWs merge_ws(int64_t n_tok, int64_t n_max, int64_t C) {
+    MergeWs W; size_t o = 0;
+    const size_t ld = (size_t)(n_max + 7) / 8 * 8;
+    W.xn = o;   o += align_up((size_t)n_tok * C * 2);
+    W.sim = o;  o += align_up((size_t)merge_group_sets(n_max) * n_max * ld * 4);
+    W.slot = o; o += align_up((size_t)n_tok * 4);
+    W.kept = o; o += align_up((size_t)n_tok);
+    W.total = o;
+    return W;
+}
+}  // namespace
+
+size_t skipffn_token_merge_workspace_bytes(int64_t n_tok, int64_t n_max, int64_t C) {
+    if (n_tok < 0 || n_max < 0 || C <= 0) return 0;
+    return merge_ws(n_tok, n_max, C).total + 256;
+}
+
+int skipffn_token_merge(const void* x, const int32_t* seg_host, int64_t S, int64_t C, int64_t k,
+                        void* out, int32_t* kept_idx, int32_t* assign, float* avg_sim,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (S < 0 || C <= 0 || k < 0) return SKIPFFN_EINVAL;
+    if (C & 7) return SKIPFFN_ESHAPE;
+    if (S == 0) return SKIPFFN_OK;
+    if (seg_host == nullptr) return SKIPFFN_EINVAL;
+    int64_t n_max = 0;
+    for (int64_t i = 0; i < S; ++i) {
+        if (seg_host[i] < 0 || seg_host[i + 1] < seg_host[i]) return SKIPFFN_EINVAL;
+        n_max = std::max<int64_t>(n_max, seg_host[i + 1] - seg_host[i]);
+    }
+    const int64_t n_tok = seg_host[S];
+    if (n_max > MERGE_MAX_N || k > MERGE_MAX_N || S > 65535) return SKIPFFN_ESHAPE;
+    if (n_tok * C * 2 >= kMaxTensorBytes || S * k * C * 2 >= kMaxTensorBytes) return SKIPFFN_ESHAPE;
+    if (k > 0 && (bad_ptr(out) || kept_idx == nullptr)) return SKIPFFN_EINVAL;
+    if (n_tok > 0 && (bad_ptr(x) || assign == nullptr || avg_sim == nullptr)) return SKIPFFN_EINVAL;
+    const MergeWs W = merge_ws(n_tok, n_max, C);
+    if (workspace == nullptr || !aligned16(workspace) || workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if ((e = ensure_gemm_init()) != hipSuccess) return hip_fail(e);
+    char* ws = static_cast<char*>(workspace);
+    bf16_t* xn = reinterpret_cast<bf16_t*>(ws + W.xn);
+    float* sim = reinterpret_cast<float*>(ws + W.sim);
+    int32_t* slot_of = reinterpret_cast<int32_t*>(ws + W.slot);
+    uint8_t* kept = reinterpret_cast<uint8_t*>(ws + W.kept);
+    const bf16_t* xb = static_cast<const bf16_t*>(x);
+    const int ld = (int)((n_max + 7) / 8 * 8);
+    const int64_t sim_stride = n_max * ld;
+    const int group = merge_group_sets(n_max);
+    profile_mark_begin(KC_MERGE, s);
+    e = launch_row_normalize(xb, n_tok, (int)C, xn, s);
+    for (int64_t g0 = 0; g0 < S && e == hipSuccess; g0 += group) {
+        SegTable st;
+        st.count = (int)std::min<int64_t>(group, S - g0);
+        int gmax = 0;
+        for (int i = 0; i <= st.count; ++i) st.off[i] = seg_host[g0 + i];
+        for (int i = st.count + 1; i <= SEG_TABLE_MAX; ++i) st.off[i] = st.off[st.count];
+        for (int i = 0; i < st.count; ++i) gmax = std::max(gmax, st.off[i + 1] - st.off[i]);
+        // S_i = Xn_i Xn_i^T  [n_i, n_i] fp32 on the MFMA core, every set of the group in one grid
+        e = launch_gemm_selfsim(xn, (int)C, st, gmax, sim, ld, sim_stride, s);
+        if (e != hipSuccess) break;
+        e = launch_merge_group(xb, st, gmax, (int)C, (int)k, (int)g0, sim, ld, sim_stride, avg_sim, kept,
+                               slot_of, kept_idx, assign, static_cast<bf16_t*>(out), s);
+    }
+    profile_mark_end(KC_MERGE, s);
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 

@@ -71,6 +71,11 @@ struct GemmArgs {
     int no_residual;             // EPI_RESID_SCATTER: 1 = do not add the residual
 };
 
+// Row offsets of up to SEG_TABLE_MAX token sets, passed by value in the kernel arguments
+// (set i = rows [off[i], off[i+1]) of a token list).
+constexpr int SEG_TABLE_MAX = 64;
+struct SegTable { int count; int off[SEG_TABLE_MAX + 1]; };
+
 // ---- LDS addressing ----------------------------------------------------------
 // The LDS of gfx950 serves 256 B per clock (64 banks of 4 B): a 16-byte read is
 // processed 16 lanes at a time, an 8-byte read 32 lanes at a time, and is free of
@@ -672,6 +677,29 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_streamk_kernel(GemmArg
         first = false;
         gemm_tile<A_KC, B_KC, EPI_PARTIAL>(P, sg.i, tn, sg.slot, sg.kb, sg.ke, Meff, Keff);
     }
+}
+
+// ---- self-similarity of several row sets in one grid: S_i = X_i X_i^T (fp32) -------------------
+// P describes the whole row list (A0 = first row, lda = row length, K = row length); item i uses
+// rows st.off[i] .. st.off[i+1]) and writes [n_i][P.ldo] floats at out0 + i * out_stride.  The
+// grid covers tiles_1d x tiles_1d tiles per item (tiles_1d from the largest set).
+template <int EPI>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_selfsim_kernel(GemmArgs P, SegTable st, int tiles_1d,
+                                                                         int64_t out_stride) {
+    const int b = (int)blockIdx.x;
+    const int per_item = tiles_1d * tiles_1d;
+    const int item = b / per_item;
+    const int r = b - item * per_item;
+    const int tn = r / tiles_1d, tm = r - tn * tiles_1d;
+    const int lo = st.off[item], n = st.off[item + 1] - lo;
+    if (tm * BM >= n || tn * BN >= n) return;        // whole block leaves together
+    P.A0 += (int64_t)lo * P.lda;
+    P.B0 = P.A0;
+    P.a_bytes = P.b_bytes = (uint32_t)((int64_t)n * P.lda * 2);
+    P.M = P.N = n;
+    P.out0 = static_cast<float*>(P.out0) + item * out_stride;
+    const int ktotal = (P.K + BK - 1) / BK;
+    gemm_tile<true, true, EPI>(P, tm, tn, 0, 0, ktotal, n, P.K);
 }
 
 }  // namespace skipffn

@@ -14,6 +14,7 @@ hipError_t gemm_init() {
     if ((e = set_lds_limit<true, true, EPI_SWIGLU>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_PARTIAL>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_STORE>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_STORE_T>()) != hipSuccess) return e;
@@ -25,6 +26,9 @@ hipError_t gemm_init() {
                             hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_streamk_kernel<true, false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_selfsim_kernel<EPI_STORE>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e != hipSuccess) return e;
     return hipSuccess;
@@ -73,12 +77,29 @@ hipError_t launch_gemm_streamk(bool a_kc, bool b_kc, GemmArgs& a, int nbg, hipSt
     return hipGetLastError();
 }
 
+hipError_t launch_gemm_selfsim(const bf16_t* xn, int C, const SegTable& st, int n_max, float* sim, int ld,
+                               int64_t sim_stride, hipStream_t s) {
+    if (st.count <= 0 || n_max <= 0) return hipSuccess;
+    GemmArgs a{};
+    a.M = n_max; a.N = n_max; a.K = C;
+    a.A0 = xn; a.lda = C; a.B0 = xn; a.ldb = C;
+    a.pairs = 1; a.splits = 1; a.batch = 1;
+    a.out0 = sim; a.ldo = ld; a.out_f32 = 1; a.accumulate = 0;
+    const int tiles_1d = (n_max + BM - 1) / BM;
+    a.tiles_m = a.tiles_n = tiles_1d;
+    const unsigned blocks = (unsigned)(st.count * tiles_1d * tiles_1d);
+    hipLaunchKernelGGL(gemm_bf16_selfsim_kernel<EPI_STORE>, dim3(blocks), dim3(GEMM_THREADS), GEMM_LDS_BYTES, s, a, st,
+                       tiles_1d, sim_stride);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s) {
     finish_args(epi, a);
     if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
     if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU>(a, s);
     if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL>(a, s);
     if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER>(a, s);
+    if (a_kc && b_kc && epi == EPI_STORE) return launch_one<true, true, EPI_STORE>(a, s);
     if (a_kc && !b_kc && epi == EPI_SWIGLU_BWD) return launch_one<true, false, EPI_SWIGLU_BWD>(a, s);
     if (a_kc && !b_kc && epi == EPI_PARTIAL) return launch_one<true, false, EPI_PARTIAL>(a, s);
     if (a_kc && !b_kc && epi == EPI_STORE_T) return launch_one<true, false, EPI_STORE_T>(a, s);

@@ -28,6 +28,7 @@ enum KernelClass : int {
     KC_SUMMARY_FWD,
     KC_SUMMARY_BWD,
     KC_SELECT,
+    KC_MERGE,
     KC_COUNT
 };
 const char* kernel_class_name(int kc);
@@ -97,6 +98,16 @@ hipError_t launch_select_retained(const bf16_t* feat, const bf16_t* cls, const i
                                   int64_t n_feat, int B, int Cv, int n_keep, const int32_t* n_keep_dev,
                                   uint8_t* mask, float* sim, const int32_t* token_pos,
                                   uint8_t* skip_mask, int64_t T, hipStream_t s);
+
+// ---- token merge -----------------------------------------------------------------------------------
+constexpr int MERGE_MAX_N = 4096;   // tokens per set (the similarity matrix is n x n fp32)
+hipError_t launch_row_normalize(const bf16_t* x, int64_t rows, int C, bf16_t* xn, hipStream_t s);
+hipError_t launch_gemm_selfsim(const bf16_t* xn, int C, const SegTable& st, int n_max, float* sim, int ld,
+                               int64_t sim_stride, hipStream_t s);
+hipError_t launch_merge_group(const bf16_t* x, const SegTable& st, int n_max, int C, int k, int set_base,
+                              const float* sim, int ld, int64_t sim_stride, float* avg, uint8_t* kept,
+                              int32_t* slot_of, int32_t* kept_idx, int32_t* assign, bf16_t* out,
+                              hipStream_t s);
 
 // ---- GEMMs -----------------------------------------------------------------------
 hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation (once per process)

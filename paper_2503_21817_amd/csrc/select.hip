@@ -71,42 +71,47 @@ __global__ __launch_bounds__(SEL_THREADS) void cls_sim_kernel(
     }
 }
 
-// ---- rank count and mask, one workgroup per sequence ------------------------------------------
+// ---- rank count and mask: a workgroup takes SEL_RANK_CH tokens of one sequence ----------------
+// Every workgroup stages the similarities of the whole sequence in LDS (up to SEL_LDS_SIMS;
+// longer sequences are read from global memory) and counts, for each of its tokens, how many
+// tokens beat it.
+constexpr int SEL_RANK_CH = SEL_THREADS;
 __global__ __launch_bounds__(SEL_THREADS) void select_topn_kernel(
-    const float* __restrict__ sim, const int32_t* __restrict__ seq_off, int n_feat, int n_keep,
+    const float* __restrict__ sim, const int32_t* __restrict__ seq_off, int B, int n_feat, int n_keep,
     const int32_t* __restrict__ n_keep_dev, uint8_t* __restrict__ mask,
     const int32_t* __restrict__ token_pos, uint8_t* __restrict__ skip_mask, int64_t T) {
     __shared__ float ssim[SEL_LDS_SIMS];
-    const int b = blockIdx.x;
+    int b, t0, nt;
+    if (!locate_chunk<SEL_RANK_CH>(seq_off, B, n_feat, (int)blockIdx.x, b, t0, nt)) return;
     int lo, hi;
     seg_bounds(seq_off, b, n_feat, lo, hi);
     const int n = hi - lo;
     const int keep = n_keep_dev != nullptr ? n_keep_dev[b] : n_keep;
     const bool in_lds = n <= SEL_LDS_SIMS;
     if (in_lds) {
-        for (int t = threadIdx.x; t < n; t += SEL_THREADS) ssim[t] = sim[lo + t];
+        for (int u = threadIdx.x; u < n; u += SEL_THREADS) ssim[u] = sim[lo + u];
         __syncthreads();
     }
-    for (int t = threadIdx.x; t < n; t += SEL_THREADS) {
-        const float st = in_lds ? ssim[t] : sim[lo + t];
-        int beats = 0;
-        if (in_lds) {
-            for (int u = 0; u < n; ++u) {
-                const float su = ssim[u];
-                beats += (su > st || (su == st && u < t)) ? 1 : 0;
-            }
-        } else {
-            for (int u = 0; u < n; ++u) {
-                const float su = sim[lo + u];
-                beats += (su > st || (su == st && u < t)) ? 1 : 0;
-            }
+    const int t = (t0 - lo) + threadIdx.x;           // index inside the sequence
+    if ((int)threadIdx.x >= nt) return;
+    const float st = in_lds ? ssim[t] : sim[lo + t];
+    int beats = 0;
+    if (in_lds) {
+        for (int u = 0; u < n; ++u) {
+            const float su = ssim[u];
+            beats += (su > st || (su == st && u < t)) ? 1 : 0;
         }
-        const uint8_t m = beats < keep ? 0 : 1;
-        mask[lo + t] = m;
-        if (skip_mask != nullptr && token_pos != nullptr) {
-            const int pos = token_pos[lo + t];
-            if ((uint32_t)pos < (uint64_t)T) skip_mask[pos] = m;
+    } else {
+        for (int u = 0; u < n; ++u) {
+            const float su = sim[lo + u];
+            beats += (su > st || (su == st && u < t)) ? 1 : 0;
         }
+    }
+    const uint8_t m = beats < keep ? 0 : 1;
+    mask[lo + t] = m;
+    if (skip_mask != nullptr && token_pos != nullptr) {
+        const int pos = token_pos[lo + t];
+        if ((int64_t)pos >= 0 && (int64_t)pos < T) skip_mask[pos] = m;
     }
 }
 
@@ -121,7 +126,8 @@ hipError_t launch_select_retained(const bf16_t* feat, const bf16_t* cls, const i
                        (int)n_feat, Cv, sim);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(select_topn_kernel, dim3((unsigned)B), dim3(SEL_THREADS), 0, s, sim, seq_off,
+        const unsigned nr = (unsigned)((n_feat + SEL_RANK_CH - 1) / SEL_RANK_CH + B);
+        hipLaunchKernelGGL(select_topn_kernel, dim3(nr), dim3(SEL_THREADS), 0, s, sim, seq_off, B,
                            (int)n_feat, n_keep, n_keep_dev, mask, token_pos, skip_mask, T);
         e = hipGetLastError();
     }

@@ -166,6 +166,25 @@ def test_select_retained_rejects_bad_arguments_on_the_host():
     assert f(FAKE, FAKE, FAKE, 10, 0, 64, 3, None, FAKE, FAKE, None, None, 0, None) == B.OK       # no sequences
 
 
+def test_token_merge_rejects_bad_arguments_on_the_host():
+    lib = B.lib()
+    f = lib.skipffn_token_merge
+    seg = (ctypes.c_int32 * 3)(0, 10, 30)
+    bad = (ctypes.c_int32 * 3)(0, 10, 5)
+    big = (ctypes.c_int32 * 2)(0, 5000)
+    BIG = 1 << 40
+    # x, seg_host, S, C, k, out, kept_idx, assign, avg_sim, workspace, workspace_bytes, stream
+    assert f(FAKE, seg, 2, 60, 4, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.ESHAPE
+    assert f(FAKE, bad, 2, 64, 4, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.EINVAL      # not ascending
+    assert f(FAKE, big, 1, 64, 4, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.ESHAPE      # set too large
+    assert f(FAKE, seg, 2, 64, -1, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.EINVAL
+    assert f(FAKE, None, 2, 64, 4, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.EINVAL
+    assert f(FAKE, seg, 2, 64, 4, None, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.EINVAL
+    assert f(FAKE, seg, 2, 64, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 64, None) == B.EWORKSPACE
+    assert f(FAKE, seg, 0, 64, 4, FAKE, FAKE, FAKE, FAKE, FAKE, BIG, None) == B.OK           # no sets
+    assert lib.skipffn_token_merge_workspace_bytes(2048, 1024, 4096) >= 2048 * 4096 * 2 + 1024 * 1024 * 4
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -1,0 +1,108 @@
+"""GPU parity of the token merge (Section 4.1) through the C ABI.  Which tokens are kept and
+where a token goes are integers decided by floating-point similarities, so those decisions are
+checked in the kernel's precision (the oracle's rule applied to the averages the GPU returns
+must give the GPU's kept set; every assignment must be optimal up to the rounding of the
+similarities, and equal to the fp64 choice wherever that choice has a clear margin); the merged
+rows are then compared with the oracle's merge of the same groups."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import skipffn_oracle as O
+from paper_2503_21817_amd import binding as B
+from helpers import REL_L2_TOL, bits_of, rel_l2, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+SIM_TOL = 6e-3        # bf16 rounding of the normalised rows: about 2^-8 on a cosine similarity
+
+
+def run_gpu(xb, seg, k):
+    n_tok, C = xb.shape
+    S = len(seg) - 1
+    n_max = max([seg[i + 1] - seg[i] for i in range(S)] + [0])
+    d_x = to_dev_bf16(xb)
+    out = torch.full((S, k, C), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kept = torch.full((S, k), -7, dtype=torch.int32, device="cuda")
+    assign = torch.full((n_tok,), -7, dtype=torch.int32, device="cuda")
+    avg = torch.full((n_tok,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.skipffn_token_merge_workspace_bytes(n_tok, n_max, C), dtype=torch.uint8, device="cuda")
+    B.skipffn_token_merge(d_x, seg, k, out, kept, assign, avg, workspace=ws)
+    torch.cuda.synchronize()
+    return bits_of(out), kept.cpu().numpy(), assign.cpu().numpy(), avg.cpu().numpy()
+
+
+def check(xb, seg, k, expect_exact=False):
+    out, kept, assign, avg = run_gpu(xb, seg, k)
+    ref = O.token_merge(xb, seg, k)
+    for s in range(len(seg) - 1):
+        lo, hi = seg[s], seg[s + 1]
+        n = hi - lo
+        kk = min(k, n)
+        if n == 0:
+            assert np.all(kept[s] == -1) and np.all(out[s] == 0)
+            continue
+        X = O.bf16_bits_to_f64(xb[lo:hi])
+        S64 = O.cosine_matrix(X)
+        assert np.allclose(avg[lo:hi], ref["avg"][lo:hi], rtol=0, atol=SIM_TOL)
+        # kept set: the oracle's rule on the GPU's own averages
+        order = np.argsort(avg[lo:hi], kind="stable")
+        want_kept = np.sort(order[:kk]) + lo
+        assert np.array_equal(kept[s, :kk], want_kept) and np.all(kept[s, kk:] == -1)
+        kloc = kept[s, :kk] - lo
+        a = assign[lo:hi]
+        assert np.array_equal(a[kloc], np.arange(kk))
+        assert np.all((a >= 0) & (a < kk))
+        # every merged token went to a kept token that is (nearly) its most similar one
+        for i in range(n):
+            if i in set(kloc.tolist()):
+                continue
+            best = S64[i, kloc].max()
+            assert S64[i, kloc[a[i]]] >= best - 2 * SIM_TOL, (s, i)
+            top2 = np.sort(S64[i, kloc])[-2:] if kk > 1 else [None, None]
+            if kk == 1 or top2[1] - top2[0] > 2 * SIM_TOL:
+                assert a[i] == int(np.argmax(S64[i, kloc])), (s, i)
+        # merged rows: the oracle's mean over the GPU's groups
+        merged = O.merge_rows(X, a, kk)
+        assert rel_l2(O.bf16_bits_to_f64(out[s, :kk]), merged) < REL_L2_TOL
+        assert np.all(out[s, kk:] == 0)
+    if expect_exact:
+        assert np.array_equal(kept, ref["kept"]) and np.array_equal(assign, ref["assign"])
+        assert rel_l2(O.bf16_bits_to_f64(out), O.bf16_bits_to_f64(ref["out_bits"])) < REL_L2_TOL
+
+
+def clustered(n, C, centers, noise, seed):
+    """Tokens scattered around a few directions: large margins in every decision."""
+    rng = np.random.default_rng(seed)
+    ctr = rng.standard_normal((centers, C))
+    lab = rng.integers(0, centers, n)
+    return O.f64_to_bf16_bits(ctr[lab] * rng.uniform(0.5, 2.0, (n, 1)) + noise * rng.standard_normal((n, C)))
+
+
+@pytest.mark.parametrize("lens,C,k", [((1024,), 1024, 256), ((300, 77, 512), 256, 64), ((40, 0, 9), 264, 16),
+                                      ((600,), 4096, 150)],
+                         ids=["paper-1024-to-256", "three-sets", "empty-and-short-sets", "backbone-width"])
+def test_merge_random_tokens(lens, C, k):
+    rng = np.random.default_rng(sum(lens) + C)
+    xb = O.f64_to_bf16_bits(rng.standard_normal((sum(lens), C)))
+    seg = [0] + np.cumsum(lens).tolist()
+    check(xb, seg, k)
+
+
+def test_merge_clustered_tokens_small_margins_inside_clusters():
+    xb = clustered(500, 512, centers=40, noise=0.05, seed=3)
+    check(xb, [0, 200, 500], 60)
+
+
+def test_duplicates_single_token_and_k_extremes():
+    rng = np.random.default_rng(9)
+    base = O.f64_to_bf16_bits(rng.standard_normal((5, 128)))
+    xb = base[[0, 1, 2, 1, 3, 0, 4, 2]]                      # exact duplicates: similarity ties
+    check(xb, [0, 8], 3)
+    check(xb, [0, 8], 8)                                     # k = n: nothing merged
+    out, kept, assign, _ = run_gpu(xb, [0, 8], 8)
+    assert np.array_equal(out[0], xb) and kept[0].tolist() == list(range(8))
+    check(xb, [0, 8], 1)                                     # k = 1: the mean of all
+    check(xb[:1], [0, 1], 4)                                 # a single token
+    out, kept, assign, _ = run_gpu(xb, [0, 8], 12)           # k > n: zero rows after the 8 tokens
+    assert np.array_equal(out[0, :8], xb) and np.all(out[0, 8:] == 0) and kept[0, 8:].tolist() == [-1] * 4
