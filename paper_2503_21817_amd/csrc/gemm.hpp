@@ -659,16 +659,34 @@ template <bool A_KC, bool B_KC>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_streamk_kernel(GemmArgs P) {
     const int nbg = P.splits;
     const int nb = (int)gridDim.x;
+    const int tiles_n = nb / nbg;
     int b = (int)blockIdx.x;
-    // workgroups are dealt round-robin to the 8 XCDs: give each XCD whole groups
+    // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of the
+    // logical order below
     if ((nb & 7) == 0) b = (b & 7) * (nb >> 3) + (b >> 3);
-    const int tn = b / nbg, j = b - tn * nbg;
     const int Meff = effective_rows(P.M, P.m_dev);
     const int Keff = effective_rows(P.K, P.k_dev);
     const int g = (Meff + BM - 1) / BM;
     const int kt = ((Keff + BK - 1) / BK) * P.pairs;
     if (g == 0 || kt == 0) return;
     const StreamKPlan p = streamk_plan(g, kt, nbg);
+    // Logical order: aligned chunks first, chunk-major, then n-tile, then m-tile - so an XCD
+    // works on ONE K range of many n-tiles (the m-tiles of an n-tile share the weight slabs,
+    // the n-tiles share the activation slabs, and no XCD streams the whole K extent of the
+    // activations); the remainder pieces follow.  (tn, j) = n-tile and workgroup index in its group.
+    int tn, j;
+    const int aligned_total = p.a * g * tiles_n;
+    if (b < aligned_total) {
+        const int c = b / (tiles_n * g);
+        const int r = b - c * (tiles_n * g);
+        tn = r / g;
+        j = c * g + (r - tn * g);
+    } else {
+        const int per = nbg - p.a * g;            // workgroups per group left for the remainder
+        const int r = b - aligned_total;
+        tn = r / per;
+        j = p.a * g + (r - tn * per);
+    }
     StreamKIter it = streamk_begin(p, j);
     StreamKSeg sg;
     bool first = true;
