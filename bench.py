@@ -31,9 +31,9 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # profiles/bench_cfg2_fwd_bwd_hbm_traffic_and_mfma_counters.md.  Counters cannot be read from
 # inside this process, so the figure is the profiled one for the same launch configuration.
 MEASURED_TRAFFIC_CFG2_FWD_BWD = {
-    "gemm_gate_up_swiglu": 685.0e6, "gemm_down": 334.6e6, "gemm_dh_swiglu_bwd+dw_down": 1027.5e6,
-    "gemm_dw_gate_up": 741.7e6, "gemm_dxn": 710.9e6, "gather_rmsnorm": 36.5e6,
-    "resid_scatter": 72.4e6, "rmsnorm_bwd_scatter": 157.0e6, "gather_rows": 30.2e6,
+    "gemm_gate_up_swiglu": 685.0e6, "gemm_down": 384.1e6, "gemm_dh_swiglu_bwd+dw_down": 998.3e6,
+    "gemm_dw_gate_up": 741.6e6, "gemm_dxn": 687.4e6, "gather_rmsnorm": 36.4e6,
+    "resid_scatter": 105.0e6, "rmsnorm_bwd_scatter": 117.2e6, "gather_rows": 30.2e6,
 }
 
 
@@ -45,7 +45,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
@@ -341,6 +341,29 @@ def merge_sweep(torch, B, args):
             "config": {"workload": "1024 -> 256 tokens per set"}, "sweep": rows}
 
 
+def copy_sweep(torch, args):
+    """A plain device copy of 1 GiB (read 1 GiB, write 1 GiB): the HBM rate this machine reaches,
+    next to the published 8 TB/s, and the kernel of known size that the FETCH_SIZE / WRITE_SIZE
+    counters are calibrated with."""
+    n = 1 << 30
+    src = torch.full((n,), 1, dtype=torch.uint8, device="cuda")
+    dst = torch.full((n,), 2, dtype=torch.uint8, device="cuda")
+    for _ in range(args.warmup):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    gbs = 2 * n / (ms * 1e-3) / 1e9
+    return {"metric": "device copy bandwidth (read + write)", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "dtype": "u8", "data": "synthetic",
+            "config": {"workload": "1 GiB device-to-device copy"}, "us": round(ms * 1e3, 1),
+            "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
+
+
 def kv_sweep(torch, B, W, args):
     """Skip KV-cache (Section 4.3) on a packed cache [layers, 2, kv heads, T, head dim] of the
     backbone (32 x 2 x 8 x T x 128, bf16): algorithmic bytes = read + write of the retained
@@ -401,6 +424,9 @@ def main():
     bwd = args.passes == "fwd+bwd"
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "copy":
+        print(json.dumps(copy_sweep(torch, args)))
         return
     if args.sweep == "merge":
         print(json.dumps(merge_sweep(torch, B, args)))
