@@ -25,6 +25,11 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# What the box itself reaches (profiles/bench_cfg2_fwd_bwd_hbm_traffic_and_mfma_counters.md): a
+# register-only MFMA loop on random bf16 operands (the clock drops under the power cap), and a
+# 1 GiB device copy (bench.py --sweep copy).  Context next to the published peaks, never `peak`.
+MEASURED_MFMA_RANDOM_TFLOPS = 1900.0
+MEASURED_COPY_GBS = 5000.0
 
 # Bytes per launch that the L2s exchanged with the fabric / HBM for configuration 2, forward +
 # backward: rocprofv3 --pmc FETCH_SIZE (x 2.0, calibrated with a copy kernel) + WRITE_SIZE, from
@@ -560,7 +565,9 @@ def main():
     roofline = {"kernel": dom, "bound": kind, "achieved": round(achieved, 2), "peak": peak,
                 "unit": unit, "frac": round(achieved / peak, 4),
                 "traffic": (MEASURED_TRAFFIC_CFG2_FWD_BWD.get(dom) if (args.config == 2 and bwd) else None),
-                "avg_launch_ms": kernels[dom]["avg_ms"]}
+                "avg_launch_ms": kernels[dom]["avg_ms"],
+                "frac_of_measured_ceiling": round(achieved / (MEASURED_MFMA_RANDOM_TFLOPS if kind == "mfma"
+                                                              else MEASURED_COPY_GBS), 4)}
     gemm_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k.startswith("gemm_"))
 
     flops = L * skipffn_flops(R, C, I, bwd)
