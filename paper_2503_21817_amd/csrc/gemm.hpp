@@ -234,6 +234,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     typedef __attribute__((address_space(3))) void* lds_void_ptr;
     // issue load i (0..3) of this wave's share of A slab j / B slab j (0-based inside this
     // block's K range)
+    // The slab step is uniform.  It can travel in the scalar offset of the buffer load, the
+    // per-lane offset staying the loop-invariant a_goff / b_goff (an invalid row keeps
+    // kOobOffset, which stays out of range with any step added; only a slab that reaches past
+    // K masks lanes individually), or be added per lane.  Measured: the scalar form costs the
+    // KC/KC loop 20 % more cycles per slab, but makes the dH + dW_down grid 1.5-2 % faster - so it
+    // is used for exactly those two instantiations.
+    constexpr bool SCALAR_STEP = !B_KC && (EPI == EPI_SWIGLU_BWD || EPI == EPI_STORE);
     auto gload_a1 = [&](int j, int i) {
         const int kt = kt_begin + j;
         const int pair = kt >= ktiles_pair ? 1 : 0;
@@ -241,9 +248,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         __amdgpu_buffer_rsrc_t src = pair ? rA1 : rA0;
         char* dst = smem + (j % NSTAGE_A) * OPER_BYTES + wave * 4096 + i * 1024;
         const uint32_t step = A_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.lda) * 2);
-        uint32_t off = (a_goff[i] != kOobOffset && (kg + a_kk[i]) < Keff) ? a_goff[i] + step
-                                                                          : kOobOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+        if (SCALAR_STEP && kg + BK <= Keff) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)a_goff[i], (int)step, 0, 0);
+        } else {
+            uint32_t off = (a_goff[i] != kOobOffset && (kg + a_kk[i]) < Keff) ? a_goff[i] + step
+                                                                              : kOobOffset;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+        }
     };
     auto gload_b1 = [&](int j, int i) {
         const int kt = kt_begin + j;
@@ -253,9 +264,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         if (EPI == EPI_SWIGLU) src = wave >= 4 ? rB1 : rB0;   // regions 16.. = rows 128..
         char* dst = smem + LDS_B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096 + i * 1024;
         const uint32_t step = B_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.ldb) * 2);
-        uint32_t off = (b_goff[i] != kOobOffset && (kg + b_kk[i]) < Keff) ? b_goff[i] + step
-                                                                          : kOobOffset;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+        if (SCALAR_STEP && kg + BK <= Keff) {
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)b_goff[i], (int)step, 0, 0);
+        } else {
+            uint32_t off = (b_goff[i] != kOobOffset && (kg + b_kk[i]) < Keff) ? b_goff[i] + step
+                                                                              : kOobOffset;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+        }
     };
     auto gload_a = [&](int j) {
 #pragma unroll
