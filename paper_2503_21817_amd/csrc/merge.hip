@@ -65,7 +65,7 @@ __global__ __launch_bounds__(MG_THREADS) void sim_rowmean_kernel(const float* __
 // ---- kept[t] = 1 iff fewer than k tokens of the set have a lower average -----------------------
 __global__ __launch_bounds__(MG_THREADS) void merge_rank_kernel(const float* __restrict__ avg, SegTable st,
                                                                 int k, uint8_t* __restrict__ kept) {
-    __shared__ float sav[MERGE_MAX_N];
+    __shared__ __align__(16) float sav[MERGE_MAX_N];
     const int set = blockIdx.y;
     const int lo = st.off[set], n = st.off[set + 1] - lo;
     if ((int)blockIdx.x * MG_THREADS >= n) return;          // uniform over the workgroup
@@ -73,12 +73,7 @@ __global__ __launch_bounds__(MG_THREADS) void merge_rank_kernel(const float* __r
     __syncthreads();
     const int t = blockIdx.x * MG_THREADS + threadIdx.x;
     if (t >= n) return;
-    const float at = sav[t];
-    int lower = 0;
-    for (int u = 0; u < n; ++u) {
-        const float au = sav[u];
-        lower += (au < at || (au == at && u < t)) ? 1 : 0;
-    }
+    const int lower = rank_in_lds<false>(sav, n, t, sav[t]);
     kept[lo + t] = lower < k ? 1 : 0;
 }
 

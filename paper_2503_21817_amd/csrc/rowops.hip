@@ -474,23 +474,31 @@ __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     }
 }
 
-// dgain[c] (+)= sum over strips of gpart[strip][c], strips added in ascending order by four
-// interleaved partial sums (fixed association).  64 columns per workgroup.
+// dgain[c] (+)= sum over strips of gpart[strip][c]: eight interleaved partial sums per column,
+// added in a fixed order (deterministic).  32 columns per workgroup.
 __global__ __launch_bounds__(ROW_THREADS) void gain_grad_reduce_kernel(
     const float* __restrict__ gpart, int Rbound, const int32_t* __restrict__ r_dev, int C,
     float* __restrict__ dgain, int accumulate) {
-    __shared__ float part4[4][64];
+    __shared__ float part8[8][32];
     const int R = effective_rows(Rbound, r_dev);
     const int nstrips = (R + GAIN_STRIP - 1) / GAIN_STRIP;
-    const int cx = threadIdx.x & 63, sy = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + cx;
-    float acc = 0.0f;
-    if (c < C)
-        for (int sidx = sy; sidx < nstrips; sidx += 4) acc += gpart[(int64_t)sidx * C + c];
-    part4[sy][cx] = acc;
+    const int cx = threadIdx.x & 31, sy = threadIdx.x >> 5;
+    const int c = blockIdx.x * 32 + cx;
+    float a0 = 0.0f, a1 = 0.0f;
+    if (c < C) {
+        int q = sy;
+        for (; q + 8 < nstrips; q += 16) {             // two loads in flight per thread
+            a0 += gpart[(int64_t)q * C + c];
+            a1 += gpart[(int64_t)(q + 8) * C + c];
+        }
+        if (q < nstrips) a0 += gpart[(int64_t)q * C + c];
+    }
+    part8[sy][cx] = a0 + a1;
     __syncthreads();
     if (sy == 0 && c < C) {
-        float v = (part4[0][cx] + part4[1][cx]) + (part4[2][cx] + part4[3][cx]);
+        float v = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v += part8[k][cx];
         dgain[c] = accumulate ? dgain[c] + v : v;
     }
 }
@@ -521,7 +529,7 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl
     }
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && gg) {
-        hipLaunchKernelGGL(gain_grad_reduce_kernel, dim3((C + 63) / 64), block, 0, s, gain_partial, R,
+        hipLaunchKernelGGL(gain_grad_reduce_kernel, dim3((C + 31) / 32), block, 0, s, gain_partial, R,
                            r_dev, C, dgain, accumulate);
         e = hipGetLastError();
     }

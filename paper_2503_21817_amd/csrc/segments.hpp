@@ -59,6 +59,20 @@ __device__ __forceinline__ void unpack8s(const u32x4& v, float* f) {
     }
 }
 
+// Number of entries u of vals[0..n) (an LDS array) that come before entry t in the order
+// "DESCENDING ? larger first : smaller first", equal values ordered by index.  (One value per
+// LDS read: a four-wide version was measured twice as slow.)
+template <bool DESCENDING>
+__device__ __forceinline__ int rank_in_lds(const float* vals, int n, int t, float vt) {
+    int before = 0;
+    for (int u = 0; u < n; ++u) {
+        const float v = vals[u];
+        const bool first = DESCENDING ? v > vt : v < vt;
+        before += (first || (v == vt && u < t)) ? 1 : 0;
+    }
+    return before;
+}
+
 __device__ __forceinline__ float block_sum256(float v, float* red) {
     v = wave_sum(v);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;

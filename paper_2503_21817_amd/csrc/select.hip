@@ -80,7 +80,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topn_kernel(
     const float* __restrict__ sim, const int32_t* __restrict__ seq_off, int B, int n_feat, int n_keep,
     const int32_t* __restrict__ n_keep_dev, uint8_t* __restrict__ mask,
     const int32_t* __restrict__ token_pos, uint8_t* __restrict__ skip_mask, int64_t T) {
-    __shared__ float ssim[SEL_LDS_SIMS];
+    __shared__ __align__(16) float ssim[SEL_LDS_SIMS];
     int b, t0, nt;
     if (!locate_chunk<SEL_RANK_CH>(seq_off, B, n_feat, (int)blockIdx.x, b, t0, nt)) return;
     int lo, hi;
@@ -97,10 +97,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topn_kernel(
     const float st = in_lds ? ssim[t] : sim[lo + t];
     int beats = 0;
     if (in_lds) {
-        for (int u = 0; u < n; ++u) {
-            const float su = ssim[u];
-            beats += (su > st || (su == st && u < t)) ? 1 : 0;
-        }
+        beats = rank_in_lds<true>(ssim, n, t, st);
     } else {
         for (int u = 0; u < n; ++u) {
             const float su = sim[lo + u];

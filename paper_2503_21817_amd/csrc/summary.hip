@@ -294,23 +294,31 @@ __global__ __launch_bounds__(SUM_THREADS) void summary_chunk_bwd_kernel(
     }
 }
 
-// dw[c] (+)= sum over all chunks of part_dw[q][c], four interleaved partial sums added in a
-// fixed order (deterministic).  64 columns per workgroup.
+// dw[c] (+)= sum over all chunks of part_dw[q][c]: eight interleaved partial sums per column,
+// added in a fixed order (deterministic).  32 columns per workgroup.
 __global__ __launch_bounds__(SUM_THREADS) void summary_dw_reduce_kernel(
     const float* __restrict__ part_dw, const int32_t* __restrict__ seg, int S, int n_tok, int nq_max,
     int C, float* __restrict__ dw, int accumulate) {
-    __shared__ float part4[4][64];
+    __shared__ float part8[8][32];
     int q0, q1;
     chunk_range<SUM_CH>(seg, S - 1, n_tok, nq_max, q0, q1);           // q1 = total number of chunks
-    const int cx = threadIdx.x & 63, sy = threadIdx.x >> 6;
-    const int c = blockIdx.x * 64 + cx;
-    float acc = 0.0f;
-    if (c < C)
-        for (int q = sy; q < q1; q += 4) acc += part_dw[(int64_t)q * C + c];
-    part4[sy][cx] = acc;
+    const int cx = threadIdx.x & 31, sy = threadIdx.x >> 5;
+    const int c = blockIdx.x * 32 + cx;
+    float a0 = 0.0f, a1 = 0.0f;
+    if (c < C) {
+        int q = sy;
+        for (; q + 8 < q1; q += 16) {                  // two loads in flight per thread
+            a0 += part_dw[(int64_t)q * C + c];
+            a1 += part_dw[(int64_t)(q + 8) * C + c];
+        }
+        if (q < q1) a0 += part_dw[(int64_t)q * C + c];
+    }
+    part8[sy][cx] = a0 + a1;
     __syncthreads();
     if (sy == 0 && c < C) {
-        const float v = (part4[0][cx] + part4[1][cx]) + (part4[2][cx] + part4[3][cx]);
+        float v = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v += part8[k][cx];
         dw[c] = accumulate ? dw[c] + v : v;
     }
 }
@@ -350,7 +358,7 @@ hipError_t launch_summary_backward(const bf16_t* hidden, int64_t T, int C, const
                        S, (int)n_tok, w, xs_f32, scores, lse, gout, grad_hidden, part_dw);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) {
-        hipLaunchKernelGGL(summary_dw_reduce_kernel, dim3((unsigned)((C + 63) / 64)), dim3(SUM_THREADS), 0,
+        hipLaunchKernelGGL(summary_dw_reduce_kernel, dim3((unsigned)((C + 31) / 32)), dim3(SUM_THREADS), 0,
                            s, part_dw, seg, S, (int)n_tok, (int)nq, C, dw, accumulate);
         e = hipGetLastError();
     }
