@@ -597,6 +597,8 @@ int skipffn_summary_forward(int64_t T, int64_t C, const void* hidden, const int3
     const SumSaved L = sum_saved(n_tok, S, C);
     char* sv = static_cast<char*>(saved);
     char* ws = static_cast<char*>(workspace);
+    // with no token rows at all every set is empty (the kernels read row 0 for an absent token)
+    if (T == 0) n_tok = 0;
     hipError_t e = launch_summary_forward(
         static_cast<const bf16_t*>(hidden), T, (int)C, tok, seg, n_tok, (int)S,
         static_cast<const bf16_t*>(w), static_cast<bf16_t*>(out),
@@ -634,6 +636,7 @@ int skipffn_summary_backward(int64_t T, int64_t C, const void* hidden, const int
     const SumSaved L = sum_saved(n_tok, S, C);
     const char* sv = static_cast<const char*>(saved);
     char* ws = static_cast<char*>(workspace);
+    if (T == 0) n_tok = 0;
     hipError_t e = launch_summary_backward(
         static_cast<const bf16_t*>(hidden), T, (int)C, tok, seg, n_tok, (int)S,
         static_cast<const bf16_t*>(w), reinterpret_cast<const float*>(sv + L.xs),

@@ -18,31 +18,54 @@ constexpr int SUM_THREADS = 256;
 static_assert(SUM_CH == 16, "four wavefronts of four tokens");
 constexpr float kNoScore = -3.0e38f;      // score of an out-of-range token index: weight 0
 
-// dots of up to four rows of `hidden` (row index < 0: skipped, result 0) with the row `b`, by
-// one wavefront; the four rows are loaded together so that their latencies overlap
+// dots of four rows of `hidden` (row index < 0: skipped, result 0) with the row `b`, by one
+// wavefront.  Loads are issued for two column steps of all four rows before any arithmetic, so
+// that ten 16-byte loads per lane are in flight (a skipped row reads row 0: always in bounds).
 __device__ __forceinline__ void wave_dot4(const bf16_t* __restrict__ hidden, int C, const int* rows,
                                           const bf16_t* __restrict__ b, int chunks, int lane, float* out) {
     const u32x4* pb = reinterpret_cast<const u32x4*>(b);
-    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int c = lane; c < chunks; c += 64) {
-        u32x4 xr[4];
+    const u32x4* pr[4];
+    float scale[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k)
-            if (rows[k] >= 0) xr[k] = *reinterpret_cast<const u32x4*>(hidden + (int64_t)rows[k] * C + c * 8);
-        float y[8];
-        unpack8s(pb[c], y);
+    for (int k = 0; k < 4; ++k) {
+        pr[k] = reinterpret_cast<const u32x4*>(hidden + (int64_t)(rows[k] >= 0 ? rows[k] : 0) * C);
+        scale[k] = rows[k] >= 0 ? 1.0f : 0.0f;
+    }
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    int c = lane;
+    for (; c + 64 < chunks; c += 128) {
+        u32x4 x0[4], x1[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { x0[k] = pr[k][c]; x1[k] = pr[k][c + 64]; }
+        const u32x4 w0 = pb[c], w1 = pb[c + 64];
+        float y0[8], y1[8];
+        unpack8s(w0, y0);
+        unpack8s(w1, y1);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            if (rows[k] >= 0) {
-                float x[8];
-                unpack8s(xr[k], x);
+            float a[8], d[8];
+            unpack8s(x0[k], a);
+            unpack8s(x1[k], d);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[k] += x[j] * y[j];
-            }
+            for (int j = 0; j < 8; ++j) acc[k] += a[j] * y0[j] + d[j] * y1[j];
+        }
+    }
+    if (c < chunks) {
+        u32x4 x0[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x0[k] = pr[k][c];
+        float y0[8];
+        unpack8s(pb[c], y0);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float a[8];
+            unpack8s(x0[k], a);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[k] += a[j] * y0[j];
         }
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) out[k] = wave_sum(acc[k]);
+    for (int k = 0; k < 4; ++k) out[k] = wave_sum(acc[k]) * scale[k];
 }
 
 // ---- forward, per chunk ---------------------------------------------------------------------
@@ -94,20 +117,26 @@ __global__ __launch_bounds__(SUM_THREADS) void summary_chunk_fwd_kernel(
         e[i] = (i < nt && rowid[i] >= 0) ? __expf(sc[i] - m) : 0.0f;
         d += e[i];
     }
-    // phase B: every thread owns 16-byte column chunks: sum_t e_t X_t
+    // phase B: every thread owns 16-byte column chunks: sum_t e_t X_t.  The sixteen row loads of
+    // a chunk are unconditional (an absent token reads row 0 with weight 0) and issued together.
+    const bf16_t* rp[SUM_CH];
+#pragma unroll
+    for (int i = 0; i < SUM_CH; ++i)
+        rp[i] = hidden + (int64_t)((i < nt && rowid[i] >= 0) ? rowid[i] : 0) * C;
     float* pa = part_acc + (int64_t)blockIdx.x * C;
     for (int c = tid; c < chunks; c += SUM_THREADS) {
+        u32x4 xr[SUM_CH];
+#pragma unroll
+        for (int i = 0; i < SUM_CH; ++i) xr[i] = *reinterpret_cast<const u32x4*>(rp[i] + c * 8);
         float acc[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = 0.0f;
 #pragma unroll
         for (int i = 0; i < SUM_CH; ++i) {
-            if (i < nt && rowid[i] >= 0) {
-                float x[8];
-                unpack8s(*reinterpret_cast<const u32x4*>(hidden + (int64_t)rowid[i] * C + c * 8), x);
+            float x[8];
+            unpack8s(xr[i], x);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j] += e[i] * x[j];
-            }
+            for (int j = 0; j < 8; ++j) acc[j] += e[i] * x[j];
         }
         f32x4 lo = {acc[0], acc[1], acc[2], acc[3]}, hi = {acc[4], acc[5], acc[6], acc[7]};
         *reinterpret_cast<f32x4*>(pa + c * 8) = lo;
