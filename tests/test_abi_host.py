@@ -185,6 +185,22 @@ def test_token_merge_rejects_bad_arguments_on_the_host():
     assert lib.skipffn_token_merge_workspace_bytes(2048, 1024, 4096) >= 2048 * 4096 * 2 + 1024 * 1024 * 4
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/skipffn.h compiles as C99 with warnings as errors, and a C object that takes the
+    address of every declared function links against libskipffn.so (no GPU call is made)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    src = os.path.join(ROOT, "tests", "cpp", "header_is_c.c")
+    obj = str(tmp_path / "h.o")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-c", src, "-o", obj],
+                   check=True)
+    so = str(tmp_path / "h.so")
+    subprocess.run(["gcc", "-shared", "-o", so, obj, B.LIB_PATH, "-Wl,--no-undefined",
+                    "-Wl,-rpath," + os.path.dirname(B.LIB_PATH)], check=True)
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
