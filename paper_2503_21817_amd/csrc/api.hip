@@ -1,12 +1,12 @@
-// C ABI of the Skip-FFN block: argument validation, workspace carving and the
-// launch sequences of forward and backward.  Declarations and the contract of
-// every entry point are in include/skipffn.h.
+// C ABI of the Skip-FFN block and of the operations around it (skip KV-cache, adaptive
+// summary layer, retained-token selection, token merge): argument validation, workspace
+// carving and the launch sequences.  Declarations and the contract of every entry point are
+// in include/skipffn.h.
+#include <algorithm>
 #include <mutex>
 #include <vector>
 
 #include "../../include/skipffn.h"
-#include <algorithm>
-
 #include "kernels.hpp"
 
 using namespace skipffn;
