@@ -5,7 +5,10 @@ A step is one pass of the whole hot path over one synthetic batch: mask
 compaction, gather + RMSNorm, gate/up GEMM + SiLU*mul, down GEMM + residual
 scatter, and the backward over retained rows (dX, dW_gate, dW_up, dW_down).
 Inputs are resident in HBM before the timed region starts.  One JSON line is
-printed (see README for the fields).
+printed: metric / value / unit / ms_per_step, the workload in `config`, `roofline` for the
+kernel class with the largest share of the step (algorithmic FLOPs or bytes over its average
+HIP-event duration, against the published peak), `kernels` (every class the same way) and
+`cpu_baseline` (the fp64 numpy oracle timed on the host cores).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--passes fwd+bwd]
 """
