@@ -48,7 +48,8 @@ constexpr int kMaxSplits = 8;
 //   splits == 1, sk_nbg == 0 : one workgroup per tile, epilogue fused
 //   splits  > 1, sk_nbg == 0 : plain split-K into `splits` fp32 slabs
 //   sk_nbg  > 0              : balanced split (gemm_bf16_streamk_kernel), sk_nbg workgroups per
-//                              n-tile group; chosen only while a group's tiles fit its workgroups
+//                              n-tile group (with more m-tiles than workgroups in a group, a
+//                              workgroup walks several tiles and only boundary tiles are shared)
 struct KPartition { int splits; int sk_nbg; };
 KPartition choose_k_partition(int tiles_m, int tiles_n, int ktiles, bool force_balanced) {
     const int tiles = tiles_m * tiles_n;
@@ -62,14 +63,17 @@ KPartition choose_k_partition(int tiles_m, int tiles_n, int ktiles, bool force_b
         if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{s, 0}; }
     }
     const int nbg = tiles_n > 0 ? 256 / tiles_n : 0;
-    if (nbg >= 1 && tiles_m <= nbg && tiles > 0) {
+    if (nbg >= 1 && tiles > 0) {
         const StreamKPlan p = streamk_plan(tiles_m, ktiles, nbg);
         if (force_balanced) return KPartition{1, nbg};
         if (p.q >= 8) {
             double slabs = 0.0;
             for (int i = 0; i < tiles_m; ++i) slabs += streamk_count(p, i);
-            // a remainder piece may run two short segments: charge a second prologue/epilogue
-            double cost = p.q + 16.0 + (p.nr > 0 ? 16.0 : 0.0) + 0.04 * slabs * tiles_n;
+            // an aligned chunk is one segment; a remainder piece runs one segment (with its own
+            // prologue and epilogue: about 5 slabs' worth, measured) per tile it touches
+            const double aligned = p.a > 0 ? p.q + 16.0 : 0.0;
+            const double pieces = p.nr > 0 ? p.qr + 16.0 + 5.0 * (p.qr / p.rem) : 0.0;
+            double cost = std::max(aligned, pieces) + 0.04 * slabs * tiles_n;
             if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{1, nbg}; }
         }
     }

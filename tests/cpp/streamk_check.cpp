@@ -9,8 +9,8 @@ using namespace skipffn;
 
 int main() {
     long cases = 0;
-    for (int g = 1; g <= 24; ++g)
-        for (int nbg = g; nbg <= 40; ++nbg)
+    for (int g = 1; g <= 40; ++g)
+        for (int nbg = 1; nbg <= 40; ++nbg)
             for (int kt = 1; kt <= 300; kt += (kt < 70 ? 1 : 7)) {
                 const StreamKPlan p = streamk_plan(g, kt, nbg);
                 if (p.a * g > nbg || p.a > kStreamKMaxAligned || (p.rem > 0 && (p.nr < 1 || p.a * g + p.nr > nbg)) ||
