@@ -61,6 +61,9 @@ def parse():
                          "2, 3 and 5; summary: the adaptive summary layer, forward and backward, on "
                          "the visual token sets of the same mixes.  The JSON line then carries a 'sweep' array")
     ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
+    ap.add_argument("--out-of-place", action="store_true",
+                    help="write to separate output / gradient tensors: skipped rows are then byte-copied "
+                         "by the passthrough kernel (in place they cost nothing)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (the per-kernel events "
                          "still come from eager launches)")
@@ -485,18 +488,22 @@ def main():
     hiddens = [hidden0.clone() for _ in range(ncopy)]
     grads = [grad0.clone() for _ in range(ncopy)] if bwd else []
 
+    oop = args.out_of_place
+    out_buf = torch.empty_like(hidden0) if oop else None
+    gout_buf = torch.empty_like(grad0) if (oop and bwd) else None
+
     def step(i):
         h = hiddens[i % ncopy]
         B.skipffn_compact(mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
         for l in range(L):
             wg, wu, wd = weights[l]
-            B.skipffn_forward(h, h, bufs.idx, R, wg, wu, wd, eps=w.eps, saved=saved[l],
+            B.skipffn_forward(h, out_buf if oop else h, bufs.idx, R, wg, wu, wd, eps=w.eps, saved=saved[l],
                               workspace=bufs.fwd_ws)
         if bwd:
             g = grads[i % ncopy]
             for l in reversed(range(L)):
                 wg, wu, wd = weights[l]
-                B.skipffn_backward(g, g, bufs.idx, R, wg, wu, wd, saved[l], *dws[l],
+                B.skipffn_backward(g, gout_buf if oop else g, bufs.idx, R, wg, wu, wd, saved[l], *dws[l],
                                    eps=w.eps, workspace=bufs.bwd_ws)
 
     for i in range(args.warmup):
@@ -582,7 +589,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": data,
         "config": {"workload": f"{w.name}: T={T} tokens, R={R} retained, C={C}, I={I}, "
-                               f"{L} layer{'s' if L > 1 else ''}, {args.passes}, in place",
+                               f"{L} layer{'s' if L > 1 else ''}, {args.passes}, {'out of place' if oop else 'in place'}",
                    "T": T, "R": R, "C": C, "I": I, "layers": L, "passes": args.passes,
                    "launch": "hip graph replay" if args.graph else "eager"},
         "pct_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
