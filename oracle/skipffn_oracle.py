@@ -1,4 +1,6 @@
-"""CPU oracle for the Skip-FFN decoder-layer block (Skip-Vision, Section 4.2).
+"""CPU oracle for the Skip-FFN decoder-layer block (Skip-Vision, Section 4.2) and for the
+operations around it: skip KV-cache (Section 4.3), adaptive summary layer (Section 4.2),
+retained-token selection and token merge (Section 4.1).
 
 TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition that the
 GPU library is checked against.  It may be imported by tests, by the smoke
@@ -39,7 +41,13 @@ float64 ops with autograd; retain-none identity; bitwise passthrough with
 NaN/Inf/-0 payloads; central finite differences for every gradient; closed
 forms (zero down-projection, constant rows, power-of-two scale invariance, a
 hand-worked C=2, I=1 example); the per-layer skip error identity of Section 5
-(Eq. 8); per-token independence.  No function here is "parity unpinned".
+(Eq. 8); per-token independence; the RMSNorm-gain gradient against finite
+differences and autograd.  The functions further down carry their own section
+comments and pins: kv_skip_cache* (numpy.delete, row loops), summary_* (closed
+forms, library softmax, fp64 autograd, finite differences), cls_similarity /
+select_top_n (closed forms, plain loops, brute-force ranking), token_merge*
+(library cosine matrix, the three steps as plain loops, closed forms, invariants).
+No function here is "parity unpinned".
 """
 
 from __future__ import annotations
@@ -47,6 +55,10 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
+    "kv_skip_cache", "kv_skip_cache_all",
+    "summary_forward_real", "summary_backward_real", "summary_forward", "summary_backward",
+    "cls_similarity", "select_top_n", "select_retained",
+    "cosine_matrix", "average_similarity", "merge_decisions", "merge_rows", "token_merge_real", "token_merge",
     "bf16_bits_to_f64",
     "f64_to_bf16_bits",
     "f64_to_f32",
