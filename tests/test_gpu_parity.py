@@ -397,3 +397,37 @@ def test_gain_gradient_with_nothing_retained_is_zero():
     gpu_backward(p, bufs, dgain=dgain)
     assert torch.count_nonzero(dgain).item() == 0
 
+
+TINY = [
+    W.small(C=8, I=8, visual=(2,), text=(1,), keep=(0,), seed=71, name="tiny-8-8-one-row"),
+    W.small(C=8, I=16, visual=(5,), text=(0,), keep=(5,), seed=72, name="tiny-8-16-all-kept"),
+    W.small(C=24, I=8, visual=(70,), text=(3,), keep=(33,), seed=73, name="tiny-24-8"),
+    W.small(C=8200, I=16, visual=(9,), text=(0,), keep=(4,), seed=74, name="wide-8200-16"),   # C beyond the register-resident row paths
+]
+
+
+@pytest.mark.parametrize("w", TINY, ids=lambda w: w.name)
+def test_smallest_and_widest_shapes(w):
+    """The minimum widths the interface allows (8), a single retained row, and a hidden size
+    beyond the register-resident row kernels (streaming paths of RMSNorm forward/backward)."""
+    p = Problem(w, unit_gain=False, with_gain_tensor=True)
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    idx = fo["idx"]
+    sk = p.mask != 0
+    out, bufs = gpu_forward(p, flags=B.FLAG_NO_RESIDUAL)
+    got = bits_of(out)
+    assert np.array_equal(got[sk], p.hidden[sk])
+    fo_nr = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps, no_residual=True)
+    assert rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo_nr["out_bits"][idx])) < REL_L2_TOL
+    out, bufs = gpu_forward(p)
+    assert rel_l2(O.bf16_bits_to_f64(bits_of(out)[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx])) < REL_L2_TOL
+    dgain = torch.zeros(w.C, dtype=torch.float32, device="cuda")
+    gh, dw = gpu_backward(p, bufs, flags=B.FLAG_DW_FP32, dgain=dgain)
+    gb = bits_of(gh)
+    assert np.array_equal(gb[sk], p.grad[sk])
+    assert rel_l2(O.bf16_bits_to_f64(gb[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
+    for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+        assert rel_l2(t.double().cpu().numpy(), bo[k]) < REL_L2_TOL, k
+    assert rel_l2(dgain.double().cpu().numpy(), bo["dgain"]) < REL_L2_TOL
+
