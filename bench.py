@@ -53,7 +53,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy", "mfma"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
@@ -352,6 +352,36 @@ def merge_sweep(torch, B, args):
             "config": {"workload": "1024 -> 256 tokens per set"}, "sweep": rows}
 
 
+def mfma_sweep(torch, B, args):
+    """What the matrix cores of this machine sustain with operands in registers (no memory traffic):
+    constant operands, then pseudo-random bf16 operands.  2 workgroups of 4 wavefronts per CU."""
+    blocks, iters = 512, 20000
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    clocks = torch.zeros(2 * blocks, dtype=torch.int64, device="cuda")
+    rows = []
+    for random_operands in (0, 1):
+        for _ in range(max(args.warmup, 1)):
+            B.skipffn_probe_mfma(blocks, iters, random_operands, out, clocks)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            B.skipffn_probe_mfma(blocks, iters, random_operands, out, clocks)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        flops = blocks * 4 * iters * 8 * 32768.0
+        c = clocks.view(blocks, 2).double()
+        ghz = float((c[:, 0].sum() / c[:, 1].sum()).item()) * 0.1       # cycles per 10 ns tick
+        rows.append({"operands": "random bf16" if random_operands else "constant 1.0",
+                     "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                     "frac_published_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "shader_clock_ghz": round(ghz, 3)})
+    return {"metric": "register-only MFMA loop", "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "512 workgroups x 4 wavefronts x 160000 v_mfma_f32_32x32x16_bf16"},
+            "sweep": rows}
+
+
 def copy_sweep(torch, args):
     """A plain device copy of 1 GiB (read 1 GiB, write 1 GiB): the HBM rate this machine reaches,
     next to the published 8 TB/s, and the kernel of known size that the FETCH_SIZE / WRITE_SIZE
@@ -435,6 +465,9 @@ def main():
     bwd = args.passes == "fwd+bwd"
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
+        return
+    if args.sweep == "mfma":
+        print(json.dumps(mfma_sweep(torch, B, args)))
         return
     if args.sweep == "copy":
         print(json.dumps(copy_sweep(torch, args)))
@@ -578,6 +611,13 @@ def main():
                 "avg_launch_ms": kernels[dom]["avg_ms"],
                 "frac_of_measured_ceiling": round(achieved / (MEASURED_MFMA_RANDOM_TFLOPS if kind == "mfma"
                                                               else MEASURED_COPY_GBS), 4)}
+    if kind == "mfma":
+        # the ceiling of THIS box, measured right after the timed region while the chip is warm:
+        # a register-only MFMA loop on random bf16 operands (no memory traffic at all)
+        live = mfma_sweep(torch, B, argparse.Namespace(steps=3, warmup=1))["sweep"][1]
+        roofline["measured_ceiling"] = live["tflops"]
+        roofline["measured_ceiling_clock_ghz"] = live["shader_clock_ghz"]
+        roofline["frac_of_measured_ceiling"] = round(achieved / live["tflops"], 4)
     gemm_ms = sum(v["ms_per_step"] for k, v in kernels.items() if k.startswith("gemm_"))
 
     flops = L * skipffn_flops(R, C, I, bwd)

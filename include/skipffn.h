@@ -247,6 +247,18 @@ const char* skipffn_status_string(int status);
 int skipffn_last_hip_error(void);     /* hipError_t of the last SKIPFFN_EHIP on this thread */
 int skipffn_version(void);            /* major * 10000 + minor * 100 + patch */
 
+/* Measurement aid, not part of the method: a register-only loop of independent
+ * v_mfma_f32_32x32x16_bf16 (no memory traffic), i.e. what the matrix cores of the chip in hand
+ * sustain - the ceiling bench.py quotes next to the published peak.  `blocks` workgroups of 4
+ * wavefronts issue iters * 8 MFMAs per wavefront (32768 FLOP each); operands are the constant
+ * 1.0 or, with random_operands != 0, pseudo-random bf16 values (the clock a power-capped chip
+ * holds depends on the data).
+ *   out     f32 [blocks * 256] device OUT (keeps the arithmetic alive)
+ *   clocks  i64 [2 * blocks]  device OUT: per workgroup, shader cycles and 100 MHz wall-clock
+ *           ticks spent in the loop (their ratio is the shader clock) */
+int skipffn_probe_mfma(int64_t blocks, int64_t iters, int random_operands, float* out, int64_t* clocks,
+                       void* stream);
+
 /* Duration in milliseconds, measured with HIP events on `stream`, of the most
  * recent launch of each hot-path kernel class since the last
  * skipffn_profile_begin.  Profiling mode records events around every kernel

@@ -56,6 +56,7 @@ _SIGNATURES = {
     "skipffn_token_merge_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
     "skipffn_token_merge": (c_int, [c_void_p, POINTER(c_int32), c_int64, c_int64, c_int64, c_void_p, c_void_p,
                                     c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "skipffn_probe_mfma": (c_int, [c_int64, c_int64, c_int, c_void_p, c_void_p, c_void_p]),
     "skipffn_saved_layout": (c_int, [c_int64, c_int64, c_int64, POINTER(c_size_t)]),
     "skipffn_status_string": (c_char_p, [c_int]),
     "skipffn_last_hip_error": (c_int, []),
@@ -254,6 +255,12 @@ def skipffn_token_merge(x, seg, k, out, kept_idx, assign, avg_sim, *, workspace=
     _check(lib().skipffn_token_merge(_ptr(x), arr, len(seg) - 1, x.shape[1], int(k), _ptr(out),
                                      _ptr(kept_idx), _ptr(assign), _ptr(avg_sim), _ptr(workspace),
                                      _nbytes(workspace), _stream()), "skipffn_token_merge")
+
+
+def skipffn_probe_mfma(blocks, iters, random_operands, out, clocks):
+    """out f32 [blocks * 256]; clocks i64 [2 * blocks] (shader cycles, 100 MHz ticks per workgroup)."""
+    _check(lib().skipffn_probe_mfma(blocks, iters, int(bool(random_operands)), _ptr(out), _ptr(clocks),
+                                    _stream()), "skipffn_probe_mfma")
 
 
 def skipffn_version() -> int:

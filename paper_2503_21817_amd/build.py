@@ -19,7 +19,7 @@ OUT = os.path.join(HERE, "libskipffn.so")
 BUILD = os.path.join(CSRC, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["api.hip", "compact.hip", "rowops.hip", "summary.hip", "select.hip", "merge.hip", "gemm_inst.hip"]
+SOURCES = ["api.hip", "compact.hip", "rowops.hip", "summary.hip", "select.hip", "merge.hip", "probe.hip", "gemm_inst.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

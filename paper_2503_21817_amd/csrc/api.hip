@@ -750,4 +750,17 @@ int skipffn_token_merge(const void* x, const int32_t* seg_host, int64_t S, int64
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 
+// ---- measurement aid ---------------------------------------------------------------------------------
+int skipffn_probe_mfma(int64_t blocks, int64_t iters, int random_operands, float* out, int64_t* clocks,
+                       void* stream) {
+    if (blocks < 0 || iters < 0 || blocks > (1 << 20) || iters > (1 << 24)) return SKIPFFN_EINVAL;
+    if (blocks == 0 || iters == 0) return SKIPFFN_OK;
+    if (out == nullptr || clocks == nullptr || (reinterpret_cast<uintptr_t>(out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(clocks) & 7u))
+        return SKIPFFN_EINVAL;
+    hipError_t e = launch_mfma_probe((int)blocks, (int)iters, random_operands ? 1 : 0, out,
+                                     reinterpret_cast<long long*>(clocks), (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
 }  // extern "C"

@@ -109,6 +109,11 @@ hipError_t launch_merge_group(const bf16_t* x, const SegTable& st, int n_max, in
                               int32_t* slot_of, int32_t* kept_idx, int32_t* assign, bf16_t* out,
                               hipStream_t s);
 
+// ---- measurement aid: register-only MFMA loop -------------------------------------------------------
+// out: blocks * 256 floats; clocks: 2 * blocks int64 (shader cycles, 100 MHz wall ticks per workgroup)
+hipError_t launch_mfma_probe(int blocks, int iters, int random_operands, float* out, long long* clocks,
+                             hipStream_t s);
+
 // ---- GEMMs -----------------------------------------------------------------------
 hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation (once per process)
 // layouts: a_kc / b_kc as in gemm.hpp

@@ -1,0 +1,76 @@
+// Measurement aid: what the matrix cores of this chip sustain with NO operand traffic at all.
+// Every wavefront keeps its A and B fragments in registers and issues independent
+// v_mfma_f32_32x32x16_bf16 back to back; operands are either one constant or pseudo-random
+// bf16 values (the power drawn by the multipliers, and with it the clock the chip can hold,
+// depends on the data).  The result is the ceiling the GEMM kernels are compared with next to
+// the published peak.  It also reports the shader clock it ran at (cycle counter against the
+// 100 MHz wall counter).
+#include "kernels.hpp"
+
+namespace skipffn {
+
+constexpr int PROBE_THREADS = 256;
+constexpr int PROBE_ACC = 8;            // independent accumulator tiles per wavefront
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
+__global__ __launch_bounds__(PROBE_THREADS) void mfma_probe_kernel(int iters, int random_operands,
+                                                                   float* __restrict__ out,
+                                                                   long long* __restrict__ clocks) {
+    const uint32_t gid = blockIdx.x * PROBE_THREADS + threadIdx.x;
+    bf16x8 a[2], b[2];
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+        u32x4 ra, rb;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (random_operands) {
+                // sign, exponent within [2^-4, 2^0), random mantissa: about N(0, 1)-like spread
+                auto val = [](uint32_t r) { return ((r & 1u) << 15) | ((0x7bu + ((r >> 1) & 3u)) << 7) | ((r >> 8) & 127u); };
+                const uint32_t h0 = probe_hash(gid * 16u + f * 8u + k), h1 = probe_hash(h0 + 0x9e3779b9u);
+                ra[k] = val(h0) | (val(h0 >> 16) << 16);
+                rb[k] = val(h1) | (val(h1 >> 16) << 16);
+            } else {
+                ra[k] = 0x3f803f80u;     // 1.0, 1.0
+                rb[k] = 0x3f803f80u;
+            }
+        }
+        a[f] = __builtin_bit_cast(bf16x8, ra);
+        b[f] = __builtin_bit_cast(bf16x8, rb);
+    }
+    f32x16 acc[PROBE_ACC];
+#pragma unroll
+    for (int t = 0; t < PROBE_ACC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+    const long long w0 = wall_clock64(), c0 = clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < PROBE_ACC; ++t)
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[t & 1], b[(t >> 1) & 1], acc[t], 0, 0, 0);
+    }
+    const long long c1 = clock64(), w1 = wall_clock64();
+    float s = 0.0f;
+#pragma unroll
+    for (int t = 0; t < PROBE_ACC; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[t][r];
+    out[gid] = s;
+    if (threadIdx.x == 0) {
+        clocks[2 * blockIdx.x] = c1 - c0;
+        clocks[2 * blockIdx.x + 1] = w1 - w0;
+    }
+}
+
+hipError_t launch_mfma_probe(int blocks, int iters, int random_operands, float* out, long long* clocks,
+                             hipStream_t s) {
+    if (blocks <= 0 || iters <= 0) return hipSuccess;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)blocks), dim3(PROBE_THREADS), 0, s, iters,
+                       random_operands, out, clocks);
+    return hipGetLastError();
+}
+
+}  // namespace skipffn
