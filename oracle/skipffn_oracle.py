@@ -46,7 +46,9 @@ differences and autograd.  The functions further down carry their own section
 comments and pins: kv_skip_cache* (numpy.delete, row loops), summary_* (closed
 forms, library softmax, fp64 autograd, finite differences), cls_similarity /
 select_top_n (closed forms, plain loops, brute-force ranking), token_merge*
-(library cosine matrix, the three steps as plain loops, closed forms, invariants).
+(library cosine matrix, the three steps as plain loops, closed forms, invariants;
+the merge gradient against central differences of the whole merge, fp64 autograd
+of an index_add mean and the adjoint identity).
 No function here is "parity unpinned".
 """
 
@@ -59,6 +61,7 @@ __all__ = [
     "summary_forward_real", "summary_backward_real", "summary_forward", "summary_backward",
     "cls_similarity", "select_top_n", "select_retained",
     "cosine_matrix", "average_similarity", "merge_decisions", "merge_rows", "token_merge_real", "token_merge",
+    "merge_rows_backward", "token_merge_backward",
     "bf16_bits_to_f64",
     "f64_to_bf16_bits",
     "f64_to_f32",
@@ -550,6 +553,37 @@ def token_merge_real(X, k):
     kept, assign = merge_decisions(S, avg, k)
     return {"merged": merge_rows(X, assign, len(kept)), "kept": kept, "assign": assign,
             "S": S, "avg": avg}
+
+
+def merge_rows_backward(dM, assign, n):
+    """Gradient of merge_rows with the assignment held fixed (the choice of kept tokens and the
+    arg-max assignment are piecewise constant in X, so they carry no gradient): slot j is the
+    mean of its c_j member rows, hence every member row receives dM[j] / c_j."""
+    dM = np.asarray(dM, dtype=np.float64)
+    cnt = np.zeros(dM.shape[0])
+    for i in range(n):
+        if assign[i] >= 0:
+            cnt[assign[i]] += 1
+    dX = np.zeros((n, dM.shape[1]))
+    for i in range(n):
+        if assign[i] >= 0:
+            dX[i] = dM[assign[i]] / cnt[assign[i]]
+    return dX
+
+
+def token_merge_backward(grad_out_bits, seg, k, assign):
+    """bf16 interface of the merge gradient over several sets: grad_out_bits uint16 [S, k, C],
+    assign int [n_tok] as returned by token_merge -> dx float64 [n_tok, C] and its bf16 bits."""
+    gb = np.asarray(grad_out_bits)
+    seg = np.asarray(seg, dtype=np.int64)
+    n_tok = int(seg[-1]) if len(seg) else 0
+    C = gb.shape[2]
+    dx = np.zeros((n_tok, C))
+    for s in range(len(seg) - 1):
+        lo, hi = seg[s], seg[s + 1]
+        if hi > lo:
+            dx[lo:hi] = merge_rows_backward(bf16_bits_to_f64(gb[s]), np.asarray(assign)[lo:hi], hi - lo)
+    return {"dx": dx, "dx_bits": f64_to_bf16_bits(dx)}
 
 
 def token_merge(x_bits, seg, k):

@@ -103,3 +103,71 @@ def test_bf16_interface():
     one = O.token_merge_real(O.bf16_bits_to_f64(xb[10:25]), 6)
     assert np.array_equal(r["kept"][2], one["kept"] + 10)
     assert np.array_equal(r["out_bits"][2], O.f64_to_bf16_bits(one["merged"]))
+
+
+# ---- gradient of the merge (decisions held fixed) -----------------------------------------------
+def test_merge_gradient_against_central_differences_of_the_whole_merge():
+    """At a generic point the kept set and the assignment do not change under a small step, so
+    the difference quotient of the COMPLETE merge (similarities, selection, assignment, mean)
+    must equal the gradient that treats the decisions as constants."""
+    rng = np.random.default_rng(5)
+    n, C, k = 9, 5, 3
+    X = rng.standard_normal((n, C))
+    r = O.token_merge_real(X, k)
+    Wt = rng.standard_normal(r["merged"].shape)          # loss = sum(merged * Wt)
+    dX = O.merge_rows_backward(Wt, r["assign"], n)
+    h = 1e-6
+    for i in range(n):
+        for c in range(C):
+            Xp = X.copy(); Xp[i, c] += h
+            Xm = X.copy(); Xm[i, c] -= h
+            rp, rm = O.token_merge_real(Xp, k), O.token_merge_real(Xm, k)
+            assert np.array_equal(rp["assign"], r["assign"]) and np.array_equal(rm["assign"], r["assign"])
+            fd = (np.sum(rp["merged"] * Wt) - np.sum(rm["merged"] * Wt)) / (2 * h)
+            assert abs(fd - dX[i, c]) < 1e-8, (i, c)
+
+
+def test_merge_gradient_against_autograd_and_the_adjoint_identity():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(6)
+    n, C, kk = 40, 6, 7
+    assign = rng.integers(-1, kk, n)
+    assign[:kk] = np.arange(kk)                          # every slot has a member
+    X = rng.standard_normal((n, C))
+    G = rng.standard_normal((kk, C))
+    dX = O.merge_rows_backward(G, assign, n)
+    # <merge_rows(X), G> == <X, backward(G)>: the backward is the transpose of the forward
+    assert abs(np.sum(O.merge_rows(X, assign, kk) * G) - np.sum(X * dX)) < 1e-12
+    # library witness: a scatter-mean built from index_add, differentiated by autograd
+    xt = torch.tensor(X, dtype=torch.float64, requires_grad=True)
+    sel = torch.tensor(np.flatnonzero(assign >= 0))
+    slot = torch.tensor(assign[assign >= 0])
+    sums = torch.zeros(kk, C, dtype=torch.float64).index_add(0, slot, xt[sel])
+    cnt = torch.zeros(kk, dtype=torch.float64).index_add(0, slot, torch.ones(len(sel), dtype=torch.float64))
+    (sums / cnt[:, None] * torch.tensor(G)).sum().backward()
+    assert np.allclose(dX, xt.grad.numpy(), rtol=0, atol=1e-14)
+    assert np.all(dX[assign < 0] == 0)
+
+
+def test_merge_gradient_closed_forms_and_bf16_interface():
+    # a set kept whole: every token is its own slot, the gradient passes through unchanged
+    rng = np.random.default_rng(7)
+    xb = O.f64_to_bf16_bits(rng.standard_normal((11, 8)))
+    seg = [0, 4, 4, 11]
+    k = 7
+    fwd = O.token_merge(xb, seg, k)
+    gb = O.f64_to_bf16_bits(rng.standard_normal((3, k, 8)))
+    bwd = O.token_merge_backward(gb, seg, k, fwd["assign"])
+    assert np.array_equal(bwd["dx_bits"][0:4], gb[0, :4])
+    assert np.array_equal(bwd["dx_bits"][4:11], gb[2, :7])
+    # k = 1: one slot holding the mean of all n tokens: every row gets grad / n
+    fwd1 = O.token_merge(xb, [0, 11], 1)
+    g1 = O.f64_to_bf16_bits(rng.standard_normal((1, 1, 8)))
+    b1 = O.token_merge_backward(g1, [0, 11], 1, fwd1["assign"])
+    assert np.allclose(b1["dx"], O.bf16_bits_to_f64(g1[0, 0])[None, :] / 11, rtol=0, atol=1e-16)
+    # column sums: the gradients handed to the members of a slot add up to the slot's gradient
+    fwd2 = O.token_merge(xb, [0, 11], 3)
+    g2 = O.f64_to_bf16_bits(rng.standard_normal((1, 3, 8)))
+    b2 = O.token_merge_backward(g2, [0, 11], 3, fwd2["assign"])
+    for j in range(3):
+        assert np.allclose(b2["dx"][fwd2["assign"] == j].sum(0), O.bf16_bits_to_f64(g2[0, j]), atol=1e-14)
