@@ -344,9 +344,21 @@ def merge_sweep(torch, B, args):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
         assert int((kept >= 0).sum().item()) == S * k
+        gout = torch.randn((S, k, C), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        gx = torch.empty_like(x)
+        for _ in range(args.warmup):
+            B.skipffn_token_merge_backward(gout, seg, assign, gx)
+        e0.record()
+        for _ in range(args.steps):
+            B.skipffn_token_merge_backward(gout, seg, assign, gx)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_b = e0.elapsed_time(e1) / args.steps
+        bwd_bytes = (S * k + S * n) * C * 2.0          # read each slot gradient once, write every row
         rows.append({"sets": S, "tokens_per_set": n, "kept": k, "C": C, "us": round(ms * 1e3, 1),
                      "us_per_set": round(ms * 1e3 / S, 1),
-                     "similarity_gemm_gflop": round(2 * n * n * C * S / 1e9, 1)})
+                     "similarity_gemm_gflop": round(2 * n * n * C * S / 1e9, 1),
+                     "bwd_us": round(ms_b * 1e3, 1), "bwd_gbs": round(bwd_bytes / (ms_b * 1e-3) / 1e9, 1)})
     return {"metric": "token merge", "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
             "dtype": "bf16 in, f32 similarities", "data": "synthetic",
             "config": {"workload": "1024 -> 256 tokens per set"}, "sweep": rows}

@@ -227,11 +227,24 @@ int skipffn_select_retained(const void* features, const void* cls, const int32_t
  *   avg_sim   f32 [n_tok] OUT     the average similarities
  *   workspace: at least skipffn_token_merge_workspace_bytes(n_tok, n_max, C), n_max = rows of
  *              the largest set
- * Forward only.  Sets are processed one after the other on the stream. */
+ * Sets are processed in groups of up to 64 per launch, in order on the stream. */
 size_t skipffn_token_merge_workspace_bytes(int64_t n_tok, int64_t n_max, int64_t C);
 int skipffn_token_merge(const void* x, const int32_t* seg_host, int64_t S, int64_t C, int64_t k,
                         void* out, int32_t* kept_idx, int32_t* assign, float* avg_sim,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Gradient of the token merge with respect to x (Section 4.1; the merged tokens feed the
+ * language model during training).  Which tokens are kept and where a token goes are piecewise
+ * constant in x and carry no gradient; a kept slot is the mean of its m members, so every
+ * member receives grad_out[slot] / m, rounded once to bf16.
+ *   grad_out  bf16 [S, k, C]      gradient of `out` (rows past a set's kept count are ignored)
+ *   seg_host, S, C, k             as in the forward call
+ *   assign    i32 [n_tok]         the forward call's output; a value outside 0 .. min(k, n)-1
+ *                                 gives a zero row
+ *   grad_x    bf16 [n_tok, C] OUT every row is written
+ * No workspace. */
+int skipffn_token_merge_backward(const void* grad_out, const int32_t* seg_host, int64_t S, int64_t C,
+                                 int64_t k, const int32_t* assign, void* grad_x, void* stream);
 
 /* ---- layout of `saved`, for tests that compare stage by stage -------------
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):

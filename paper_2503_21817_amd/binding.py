@@ -56,6 +56,8 @@ _SIGNATURES = {
     "skipffn_token_merge_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
     "skipffn_token_merge": (c_int, [c_void_p, POINTER(c_int32), c_int64, c_int64, c_int64, c_void_p, c_void_p,
                                     c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]),
+    "skipffn_token_merge_backward": (c_int, [c_void_p, POINTER(c_int32), c_int64, c_int64, c_int64, c_void_p,
+                                             c_void_p, c_void_p]),
     "skipffn_probe_mfma": (c_int, [c_int64, c_int64, c_int, c_void_p, c_void_p, c_void_p]),
     "skipffn_saved_layout": (c_int, [c_int64, c_int64, c_int64, POINTER(c_size_t)]),
     "skipffn_status_string": (c_char_p, [c_int]),
@@ -255,6 +257,16 @@ def skipffn_token_merge(x, seg, k, out, kept_idx, assign, avg_sim, *, workspace=
     _check(lib().skipffn_token_merge(_ptr(x), arr, len(seg) - 1, x.shape[1], int(k), _ptr(out),
                                      _ptr(kept_idx), _ptr(assign), _ptr(avg_sim), _ptr(workspace),
                                      _nbytes(workspace), _stream()), "skipffn_token_merge")
+
+
+def skipffn_token_merge_backward(grad_out, seg, assign, grad_x):
+    """grad_out bf16 [S, k, C]; seg: host sequence of S + 1 offsets; assign i32 [n_tok] from the
+    forward call; grad_x bf16 [n_tok, C]."""
+    seg = [int(v) for v in seg]
+    arr = (c_int32 * len(seg))(*seg)
+    _check(lib().skipffn_token_merge_backward(_ptr(grad_out), arr, len(seg) - 1, grad_out.shape[2],
+                                              grad_out.shape[1], _ptr(assign), _ptr(grad_x), _stream()),
+           "skipffn_token_merge_backward")
 
 
 def skipffn_probe_mfma(blocks, iters, random_operands, out, clocks):

@@ -750,6 +750,39 @@ int skipffn_token_merge(const void* x, const int32_t* seg_host, int64_t S, int64
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 
+int skipffn_token_merge_backward(const void* grad_out, const int32_t* seg_host, int64_t S, int64_t C,
+                                 int64_t k, const int32_t* assign, void* grad_x, void* stream) {
+    if (S < 0 || C <= 0 || k < 0) return SKIPFFN_EINVAL;
+    if (C & 7) return SKIPFFN_ESHAPE;
+    if (S == 0) return SKIPFFN_OK;
+    if (seg_host == nullptr) return SKIPFFN_EINVAL;
+    int64_t n_max = 0;
+    for (int64_t i = 0; i < S; ++i) {
+        if (seg_host[i] < 0 || seg_host[i + 1] < seg_host[i]) return SKIPFFN_EINVAL;
+        n_max = std::max<int64_t>(n_max, seg_host[i + 1] - seg_host[i]);
+    }
+    const int64_t n_tok = seg_host[S];
+    if (n_max > MERGE_MAX_N || k > MERGE_MAX_N || S > 65535) return SKIPFFN_ESHAPE;
+    if (n_tok * C * 2 >= kMaxTensorBytes || S * k * C * 2 >= kMaxTensorBytes) return SKIPFFN_ESHAPE;
+    if (n_max == 0) return SKIPFFN_OK;
+    if (bad_ptr(grad_x) || assign == nullptr || (k > 0 && bad_ptr(grad_out))) return SKIPFFN_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    profile_mark_begin(KC_MERGE, s);
+    for (int64_t g0 = 0; g0 < S && e == hipSuccess; g0 += SEG_TABLE_MAX) {
+        SegTable st;
+        st.count = (int)std::min<int64_t>(SEG_TABLE_MAX, S - g0);
+        int gmax = 0;
+        for (int i = 0; i <= st.count; ++i) st.off[i] = seg_host[g0 + i];
+        for (int i = st.count + 1; i <= SEG_TABLE_MAX; ++i) st.off[i] = st.off[st.count];
+        for (int i = 0; i < st.count; ++i) gmax = std::max(gmax, st.off[i + 1] - st.off[i]);
+        e = launch_merge_bwd_group(static_cast<const bf16_t*>(grad_out), st, gmax, (int)C, (int)k, (int)g0,
+                                   assign, static_cast<bf16_t*>(grad_x), s);
+    }
+    profile_mark_end(KC_MERGE, s);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
 // ---- measurement aid ---------------------------------------------------------------------------------
 int skipffn_probe_mfma(int64_t blocks, int64_t iters, int random_operands, float* out, int64_t* clocks,
                        void* stream) {

@@ -108,6 +108,8 @@ hipError_t launch_merge_group(const bf16_t* x, const SegTable& st, int n_max, in
                               const float* sim, int ld, int64_t sim_stride, float* avg, uint8_t* kept,
                               int32_t* slot_of, int32_t* kept_idx, int32_t* assign, bf16_t* out,
                               hipStream_t s);
+hipError_t launch_merge_bwd_group(const bf16_t* dout, const SegTable& st, int n_max, int C, int k, int set_base,
+                                  const int32_t* assign, bf16_t* dx, hipStream_t s);
 
 // ---- measurement aid: register-only MFMA loop -------------------------------------------------------
 // out: blocks * 256 floats; clocks: 2 * blocks int64 (shader cycles, 100 MHz wall ticks per workgroup)

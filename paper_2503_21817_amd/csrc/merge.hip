@@ -191,7 +191,60 @@ __global__ __launch_bounds__(MG_THREADS) void merge_mean_kernel(const bf16_t* __
     }
 }
 
+// ---- gradient of the mean: dx[t] = dout[set][assign[t]] / (members of that slot) ---------------
+// The kept set and the assignment are piecewise constant in x and carry no gradient.  Every
+// workgroup recounts the members per slot of its set in LDS (integer adds: order-free), then
+// its wavefronts write MB_ROWS rows.
+constexpr int MB_ROWS = 16;
+
+__global__ __launch_bounds__(MG_THREADS) void merge_bwd_kernel(const bf16_t* __restrict__ dout, SegTable st,
+                                                               int C, int k, int set_base,
+                                                               const int32_t* __restrict__ assign,
+                                                               bf16_t* __restrict__ dx) {
+    __shared__ int cnt[MERGE_MAX_N];
+    const int set = blockIdx.y;
+    const int lo = st.off[set], n = st.off[set + 1] - lo;
+    const int r0 = blockIdx.x * MB_ROWS;
+    if (r0 >= n) return;
+    const int kk = k < n ? k : n;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, chunks = C >> 3;
+    for (int j = tid; j < kk; j += MG_THREADS) cnt[j] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += MG_THREADS) {
+        const int a = assign[lo + i];
+        if (a >= 0 && a < kk) atomicAdd(&cnt[a], 1);
+    }
+    __syncthreads();
+    for (int r = r0 + wave; r < r0 + MB_ROWS && r < n; r += 4) {
+        const int a = assign[lo + r];
+        u32x4* dst = reinterpret_cast<u32x4*>(dx + (int64_t)(lo + r) * C);
+        if (a < 0 || a >= kk) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            for (int c = lane; c < chunks; c += 64) dst[c] = z;
+            continue;
+        }
+        const float m = (float)cnt[a];
+        const u32x4* src = reinterpret_cast<const u32x4*>(dout + ((int64_t)(set_base + set) * k + a) * C);
+        for (int c = lane; c < chunks; c += 64) {
+            float f[8];
+            unpack8s(src[c], f);
+            u32x4 pk;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pk[j] = pack_bf16x2(f[2 * j] / m, f[2 * j + 1] / m);
+            dst[c] = pk;
+        }
+    }
+}
+
 // ---- launchers ---------------------------------------------------------------------------------------
+hipError_t launch_merge_bwd_group(const bf16_t* dout, const SegTable& st, int n_max, int C, int k, int set_base,
+                                  const int32_t* assign, bf16_t* dx, hipStream_t s) {
+    if (st.count == 0 || n_max <= 0) return hipSuccess;
+    hipLaunchKernelGGL(merge_bwd_kernel, dim3((unsigned)((n_max + MB_ROWS - 1) / MB_ROWS), (unsigned)st.count),
+                       dim3(MG_THREADS), 0, s, dout, st, C, k, set_base, assign, dx);
+    return hipGetLastError();
+}
+
 hipError_t launch_row_normalize(const bf16_t* x, int64_t rows, int C, bf16_t* xn, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
     hipLaunchKernelGGL(row_normalize_kernel, dim3((unsigned)rows), dim3(MG_THREADS), 0, s, x, C, xn);

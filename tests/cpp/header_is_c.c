@@ -12,6 +12,7 @@ fn skipffn_entry_points[] = {
     (fn)skipffn_summary_forward, (fn)skipffn_summary_backward,
     (fn)skipffn_select_retained,
     (fn)skipffn_token_merge_workspace_bytes, (fn)skipffn_token_merge,
+    (fn)skipffn_token_merge_backward,
     (fn)skipffn_probe_mfma,
     (fn)skipffn_saved_layout, (fn)skipffn_status_string, (fn)skipffn_last_hip_error,
     (fn)skipffn_version, (fn)skipffn_profile_begin, (fn)skipffn_profile_end,

@@ -185,6 +185,25 @@ def test_token_merge_rejects_bad_arguments_on_the_host():
     assert lib.skipffn_token_merge_workspace_bytes(2048, 1024, 4096) >= 2048 * 4096 * 2 + 1024 * 1024 * 4
 
 
+def test_token_merge_backward_rejects_bad_arguments_on_the_host():
+    f = B.lib().skipffn_token_merge_backward
+    seg = (ctypes.c_int32 * 3)(0, 10, 30)
+    bad = (ctypes.c_int32 * 3)(0, 10, 5)
+    big = (ctypes.c_int32 * 2)(0, 5000)
+    empty = (ctypes.c_int32 * 3)(4, 4, 4)
+    # grad_out, seg_host, S, C, k, assign, grad_x, stream
+    assert f(FAKE, seg, 2, 60, 4, FAKE, FAKE, None) == B.ESHAPE
+    assert f(FAKE, bad, 2, 64, 4, FAKE, FAKE, None) == B.EINVAL
+    assert f(FAKE, big, 1, 64, 4, FAKE, FAKE, None) == B.ESHAPE
+    assert f(FAKE, seg, 2, 64, -1, FAKE, FAKE, None) == B.EINVAL
+    assert f(FAKE, None, 2, 64, 4, FAKE, FAKE, None) == B.EINVAL
+    assert f(FAKE, seg, 2, 64, 4, None, FAKE, None) == B.EINVAL
+    assert f(FAKE, seg, 2, 64, 4, FAKE, None, None) == B.EINVAL
+    assert f(None, seg, 2, 64, 4, FAKE, FAKE, None) == B.EINVAL
+    assert f(None, seg, 0, 64, 4, None, None, None) == B.OK           # no sets
+    assert f(None, empty, 2, 64, 4, None, None, None) == B.OK         # only empty sets
+
+
 def test_header_is_plain_c_and_links_against_the_library(tmp_path):
     """include/skipffn.h compiles as C99 with warnings as errors, and a C object that takes the
     address of every declared function links against libskipffn.so (no GPU call is made)."""

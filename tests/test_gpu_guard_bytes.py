@@ -138,6 +138,10 @@ def test_token_merge_stays_inside_its_buffers(sizes, C, k):
     B.skipffn_token_merge(x, seg, k, g["out"].typed(torch.bfloat16, (S, k, C)),
                           g["kept"].typed(torch.int32, (S, k)), g["assign"].typed(torch.int32, (n_tok,)),
                           g["avg"].typed(torch.float32, (n_tok,)), workspace=g["ws"].view)
+    gout = torch.randn(S, k, C, device="cuda").to(torch.bfloat16)
+    g["gx"] = Guarded(2 * n_tok * C, "merge grad_x")
+    B.skipffn_token_merge_backward(gout, seg, g["assign"].typed(torch.int32, (n_tok,)),
+                                   g["gx"].typed(torch.bfloat16, (n_tok, C)))
     torch.cuda.synchronize()
     for v in g.values():
         v.check()

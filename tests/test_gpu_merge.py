@@ -106,3 +106,56 @@ def test_duplicates_single_token_and_k_extremes():
     check(xb[:1], [0, 1], 4)                                 # a single token
     out, kept, assign, _ = run_gpu(xb, [0, 8], 12)           # k > n: zero rows after the 8 tokens
     assert np.array_equal(out[0, :8], xb) and np.all(out[0, 8:] == 0) and kept[0, 8:].tolist() == [-1] * 4
+
+
+# ---- gradient ------------------------------------------------------------------------------------
+def run_gpu_backward(gb, seg, assign, n_tok, C):
+    d_g = to_dev_bf16(gb)
+    d_a = torch.from_numpy(np.asarray(assign, dtype=np.int32)).cuda()
+    gx = torch.full((max(n_tok, 1), C), float("nan"), dtype=torch.bfloat16, device="cuda")[:n_tok]
+    B.skipffn_token_merge_backward(d_g, seg, d_a, gx)
+    torch.cuda.synchronize()
+    return bits_of(gx)
+
+
+@pytest.mark.parametrize("lens,C,k", [((1024,), 1024, 256), ((300, 77, 512), 256, 64), ((40, 0, 9), 264, 16),
+                                      ((600,), 4096, 150), ((3,) * 70, 128, 2)],
+                         ids=["paper-1024-to-256", "three-sets", "empty-and-short-sets", "backbone-width",
+                              "more-sets-than-one-launch-takes"])
+def test_merge_gradient(lens, C, k):
+    """The gradient for the groups the GPU's own forward formed, against the oracle's gradient
+    for those groups: one division and one rounding per element."""
+    rng = np.random.default_rng(sum(lens) + C + 1)
+    n_tok = sum(lens)
+    xb = O.f64_to_bf16_bits(rng.standard_normal((n_tok, C)))
+    seg = [0] + np.cumsum(lens).tolist()
+    _, _, assign, _ = run_gpu(xb, seg, k)
+    gb = O.f64_to_bf16_bits(rng.standard_normal((len(lens), k, C)))
+    got = run_gpu_backward(gb, seg, assign, n_tok, C)
+    ref = O.token_merge_backward(gb, seg, k, assign)
+    g64 = O.bf16_bits_to_f64(got)
+    assert rel_l2(g64, ref["dx"]) < REL_L2_TOL
+    # element by element: float32 quotient rounded to bf16 against the exact quotient rounded to
+    # bf16 - equal except where the exact quotient sits within 2^-24 of a rounding boundary
+    same = got == ref["dx_bits"]
+    assert same.mean() > 0.9999
+    assert np.all(np.abs(g64 - ref["dx"]) <= np.abs(ref["dx"]) * 2.0 ** -8 + 1e-30)
+    # the members of a slot share its gradient: they add up to it (up to their roundings)
+    for s in range(len(lens)):
+        lo, hi = seg[s], seg[s + 1]
+        kk = min(k, hi - lo)
+        for j in range(min(kk, 5)):
+            mem = np.flatnonzero(assign[lo:hi] == j) + lo
+            tot = g64[mem].sum(0)
+            assert np.allclose(tot, O.bf16_bits_to_f64(gb[s, j]), rtol=2.0 ** -7, atol=1e-6)
+
+
+def test_merge_gradient_passes_through_a_set_kept_whole_and_zeroes_invalid_slots():
+    rng = np.random.default_rng(21)
+    gb = O.f64_to_bf16_bits(rng.standard_normal((2, 8, 64)))
+    assign = np.array([0, 1, 2, 3, 4,   2, -1, 0, 9, 0, 2], dtype=np.int32)     # sets of 5 and 6 rows
+    got = run_gpu_backward(gb, [0, 5, 11], assign, 11, 64)
+    assert np.array_equal(got[:5], gb[0, :5])                                   # identity, bit for bit
+    assert np.all(got[6] == 0) and np.all(got[8] == 0)                          # -1 and an index >= min(k, n)
+    ref = O.token_merge_backward(gb, [0, 5, 11], 8, np.where((assign < 0) | (assign > 5), -1, assign))
+    assert np.array_equal(got, ref["dx_bits"])
