@@ -105,3 +105,94 @@ def test_prefill_pipeline(visual, text, keep, C, I, Cv, layers):
     # ---- the cache without the skipped tokens ----
     assert np.array_equal(bits_of(d_small[..., :R, :]), O.kv_skip_cache_all(cache, g_skip))
     assert bool(torch.isnan(d_small[..., R:, :]).all())                 # rows past R untouched
+
+
+def test_training_step_pipeline():
+    """One training step through the same pieces: summary token written into the sequence, two
+    Skip-FFN blocks forward with saved activations, backward through both, and the gradient at the
+    summary position sent back through the summary layer into the visual tokens and its weight."""
+    visual, text, keep, C, I, layers = (300, 411), (20, 35), (75, 103), 512, 1368, 2
+    print(f"training pipeline visual={visual} text={text} keep={keep} C={C} I={I} layers={layers}", flush=True)
+    rng = np.random.default_rng(77)
+    nb = len(visual)
+    vis_pos, sum_pos, skip_np = [], [], []
+    t = 0
+    for b in range(nb):
+        vis_pos.append(np.arange(t, t + visual[b]))
+        m = np.ones(visual[b], np.uint8)
+        m[rng.permutation(visual[b])[:keep[b]]] = 0
+        skip_np += [m, np.zeros(1 + text[b], np.uint8)]
+        sum_pos.append(t + visual[b])
+        t += visual[b] + 1 + text[b]
+    T = t
+    skip_np = np.concatenate(skip_np)
+    seg = np.concatenate([[0], np.cumsum(visual)]).astype(np.int32)
+    tok = np.concatenate(vis_pos).astype(np.int32)
+    hidden = O.f64_to_bf16_bits(rng.standard_normal((T, C)))
+    grad_top = O.f64_to_bf16_bits(rng.standard_normal((T, C)))
+    w_sum = O.f64_to_bf16_bits(rng.standard_normal(C) * 0.05)
+    weights = [tuple(O.f64_to_bf16_bits(rng.standard_normal(shape) * 0.02)
+                     for shape in ((I, C), (I, C), (C, I))) for _ in range(layers)]
+    d_sum_pos = torch.tensor(sum_pos, device="cuda")
+
+    # ---- GPU ----
+    d_h0 = to_dev_bf16(hidden)
+    d_tok, d_seg, d_wsum = torch.from_numpy(tok).cuda(), torch.from_numpy(seg).cuda(), to_dev_bf16(w_sum)
+    n_tok = len(tok)
+    sv_sum = torch.empty(B.skipffn_summary_saved_bytes(n_tok, nb, C), dtype=torch.uint8, device="cuda")
+    ws_sum = torch.empty(B.skipffn_summary_workspace_bytes(n_tok, nb, C), dtype=torch.uint8, device="cuda")
+    d_s = torch.empty((nb, C), dtype=torch.bfloat16, device="cuda")
+    B.skipffn_summary_forward(d_h0, d_tok, d_seg, d_wsum, d_s, saved=sv_sum, workspace=ws_sum)
+    d_h = d_h0.clone()
+    d_h[d_sum_pos] = d_s
+    d_skip = torch.from_numpy(skip_np).cuda()
+    R = int((skip_np == 0).sum())
+    bufs = [B.SkipFFNBuffers(T, R, C, I, training=True) for _ in range(layers)]
+    B.skipffn_compact(d_skip, bufs[0].idx, bufs[0].num_retained, None, bufs[0].compact_ws)
+    idx = bufs[0].idx
+    dws = []
+    d_w = [tuple(to_dev_bf16(a) for a in wl) for wl in weights]
+    for l in range(layers):
+        B.skipffn_forward(d_h, d_h, idx, R, *d_w[l], saved=bufs[l].saved, workspace=bufs[l].fwd_ws)
+    d_g = to_dev_bf16(grad_top)
+    for l in reversed(range(layers)):
+        dw = [torch.empty((I, C), dtype=torch.float32, device="cuda"), torch.empty((I, C), dtype=torch.float32, device="cuda"),
+              torch.empty((C, I), dtype=torch.float32, device="cuda")]
+        B.skipffn_backward(d_g, d_g, idx, R, *d_w[l], bufs[l].saved, *dw, workspace=bufs[l].bwd_ws,
+                           flags=B.FLAG_DW_FP32)
+        dws.append(dw)
+    dws.reverse()
+    d_gs = d_g[d_sum_pos].contiguous()
+    d_g[d_sum_pos] = 0                                  # the rows the summary replaced get no gradient
+    d_dwsum = torch.empty(C, dtype=torch.float32, device="cuda")
+    B.skipffn_summary_backward(d_h0, d_tok, d_seg, d_wsum, sv_sum, d_gs, d_g, d_dwsum, workspace=ws_sum)
+    torch.cuda.synchronize()
+
+    # ---- the same composition of the oracle ----
+    s = O.summary_forward(hidden, tok, seg, w_sum)
+    h = hidden.copy()
+    h[sum_pos] = s["out_bits"]
+    hs = [h]
+    for wl in weights:
+        hs.append(O.skipffn_forward(hs[-1], skip_np, *wl)["out_bits"])
+    g = grad_top
+    ref_dw = []
+    for l in reversed(range(layers)):
+        b = O.skipffn_backward(hs[l], skip_np, *weights[l], g)
+        ref_dw.append(b)
+        g = b["dx_bits"]
+    ref_dw.reverse()
+    gs = g[sum_pos].copy()
+    g = g.copy()
+    g[sum_pos] = 0
+    sb = O.summary_backward(hidden, tok, seg, w_sum, gs, g)
+
+    assert rel_l2(O.bf16_bits_to_f64(bits_of(d_h)), O.bf16_bits_to_f64(hs[-1])) < REL_L2_TOL
+    got_g = bits_of(d_g)
+    assert rel_l2(O.bf16_bits_to_f64(got_g), O.bf16_bits_to_f64(sb["gh_bits"])) < REL_L2_TOL
+    # the rows the summary tokens replaced carry exactly zero
+    assert np.all(got_g[sum_pos] == 0)
+    for l in range(layers):
+        for name, got in zip(("dw_gate", "dw_up", "dw_down"), dws[l]):
+            assert rel_l2(got.cpu().numpy().astype(np.float64), ref_dw[l][name]) < REL_L2_TOL, (l, name)
+    assert rel_l2(d_dwsum.cpu().numpy().astype(np.float64), sb["dw"]) < 2 * REL_L2_TOL
