@@ -53,7 +53,7 @@ def parse():
     ap.add_argument("--config", type=int, default=2,
                     help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
                          "backward 32..1)")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy", "mfma"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy", "mfma", "prefill"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
@@ -199,6 +199,48 @@ def retention_sweep(torch, B, W, w, bwd, args):
                                    "in place"},
             "sweep": rows, "fit_ms": {"intercept": round(float(intercept), 4),
                                       "per_1000_retained": round(float(slope) * 1e3, 4)}}
+
+
+def prefill_sweep(torch, B, args):
+    """Inference prefill of one Skip-FFN block (forward only, nothing saved, in place) at small
+    batches: LLaVA-shaped sequences of 576 visual + 40 text tokens with 144 visual tokens
+    retained, and one LLaVA-HD sequence (2880 + 64 tokens, 576 retained).  With few rows the
+    block is bound by streaming the 352 MB of weights once, so the rate at which it does that is
+    reported next to the time."""
+    C, I = 4096, 14336
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4100)
+    ws = [(torch.randn(shape, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+          for shape in ((I, C), (I, C), (C, I))]
+    rows = []
+    for name, nseq, V, Tx, keep in (("llava-b1", 1, 576, 40, 144), ("llava-b2", 2, 576, 40, 144),
+                                    ("llava-b4", 4, 576, 40, 144), ("llava-b8", 8, 576, 40, 144),
+                                    ("llava-hd-b1", 1, 2880, 64, 576)):
+        T, R = nseq * (V + Tx), nseq * (keep + Tx)
+        mask_np = np.ones(T, np.uint8)
+        rng = np.random.default_rng(4100 + T)
+        for b in range(nseq):
+            base = b * (V + Tx)
+            mask_np[base + rng.choice(V, size=keep, replace=False)] = 0
+            mask_np[base + V:base + V + Tx] = 0
+        mask = torch.from_numpy(mask_np).cuda()
+        hidden = torch.randn((T, C), generator=g, device="cuda").to(torch.bfloat16)
+        copies = [hidden.clone() for _ in range(4)]
+        bufs = B.SkipFFNBuffers(T, R, C, I, training=False)
+
+        def step(i):
+            h = copies[i % 4]
+            B.skipffn_compact(mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+            B.skipffn_forward(h, h, bufs.idx, R, *ws, workspace=bufs.fwd_ws)
+
+        ms = _time_steps(torch, step, args.warmup, args.steps)
+        rows.append({"workload": name, "T": T, "R": R, "us": round(ms * 1e3, 1),
+                     "tflops": round(6.0 * R * C * I / (ms * 1e-3) / 1e12, 1),
+                     "weights_tbs": round(3.0 * C * I * 2 / (ms * 1e-3) / 1e12, 2)})
+    return {"metric": "Skip-FFN prefill (forward only) time", "unit": "us", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "C=4096, I=14336, 1 layer, forward only, in place, nothing saved"},
+            "sweep": rows}
 
 
 def compact_sweep(torch, B, args):
@@ -480,6 +522,9 @@ def main():
         return
     if args.sweep == "mfma":
         print(json.dumps(mfma_sweep(torch, B, args)))
+        return
+    if args.sweep == "prefill":
+        print(json.dumps(prefill_sweep(torch, B, args)))
         return
     if args.sweep == "copy":
         print(json.dumps(copy_sweep(torch, args)))

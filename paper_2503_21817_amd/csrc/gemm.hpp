@@ -69,6 +69,7 @@ struct GemmArgs {
     int out_f32;                 // EPI_STORE: 1 = fp32 output
     int accumulate;              // EPI_STORE: 1 = +=
     int no_residual;             // EPI_RESID_SCATTER: 1 = do not add the residual
+    int narrow;                  // host side: 1 = launch the 128-row tile variant (tiles_m counts 128-row tiles)
 };
 
 // Row offsets of up to SEG_TABLE_MAX token sets, passed by value in the kernel arguments
@@ -171,10 +172,20 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 
 // One output tile (tm, tn) over the K slabs [kt_begin, kt_end) of the concatenated pairs;
 // z selects the fp32 slab an EPI_PARTIAL result goes to.
-template <bool A_KC, bool B_KC, int EPI>
+//
+// NARROW: the tile is 128 rows tall (for GEMMs with few rows: twice the workgroups per row of
+// tiles, half the MFMA work per slab, so that the loop is bound by streaming B).  The eight
+// waves keep their 2 x 4 arrangement, each owning 64 x 64 = 2 x 2 MFMA tiles; only the first
+// 16 KB of an A stage are used.  KC A operands only.
+template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const int tn, const int z,
                                           const int kt_begin, const int kt_end, const int Meff,
                                           const int Keff) {
+    static_assert(!NARROW || (A_KC && EPI != EPI_STORE_T), "the 128-row variant takes KC A operands");
+    constexpr int TM = NARROW ? BM / 2 : BM;        // tile rows
+    constexpr int WROWS = TM / 2;                   // rows per wave row group
+    constexpr int MT = WROWS / 32;                  // MFMA tiles per wave along M
+    constexpr int A_LOADS = TM / 64;                // 1 KB regions of an A slab each wave fills
     extern __shared__ __align__(16) char smem[];
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -182,7 +193,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     const int wm = wave >> 2;      // 0..1
     const int wn = wave & 3;       // 0..3
 
-    const int m0 = tm * BM;
+    const int m0 = tm * TM;
     const int n0 = (EPI == EPI_SWIGLU) ? tn * (BN / 2) : tn * BN;
     const int ktiles_pair = (Keff + BK - 1) / BK;
     const int nk = kt_end > kt_begin ? kt_end - kt_begin : 0;
@@ -206,7 +217,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     for (int i = 0; i < 4; ++i) {
         const int q = wave * 4 + i;
         if (A_KC) {
-            int row = 8 * q + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
+            const int qa = wave * A_LOADS + i;      // regions of A: wave w owns A_LOADS consecutive ones
+            int row = 8 * qa + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
             int gr = m0 + row;
             a_goff[i] = gr < Meff ? (uint32_t)(((int64_t)gr * P.lda + c * 8) * 2) : kOobOffset;
             a_kk[i] = c * 8;
@@ -246,7 +258,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         const int pair = kt >= ktiles_pair ? 1 : 0;
         const int kg = (kt - pair * ktiles_pair) * BK;  // k offset inside the pair
         __amdgpu_buffer_rsrc_t src = pair ? rA1 : rA0;
-        char* dst = smem + (j % NSTAGE_A) * OPER_BYTES + wave * 4096 + i * 1024;
+        char* dst = smem + (j % NSTAGE_A) * OPER_BYTES + wave * (A_LOADS * 1024) + i * 1024;
         const uint32_t step = A_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.lda) * 2);
         if (SCALAR_STEP && kg + BK <= Keff) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)a_goff[i], (int)step, 0, 0);
@@ -274,16 +286,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     };
     auto gload_a = [&](int j) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) gload_a1(j, i);
+        for (int i = 0; i < A_LOADS; ++i) gload_a1(j, i);
     };
     auto gload_b = [&](int j) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) gload_b1(j, i);
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[MT][2];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
 #pragma unroll
@@ -319,16 +331,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         // A(j-1), B(j-1)) were last read in phase p-1.  Before the barrier that ends
         // phase p+3 every wave waits until only its B(j+2) loads may still be in
         // flight, so A(j+1) and B(j+1) are visible to all waves from phase p+4 on.
-        bf16x8 af[2][4], bfr[2][2];
+        bf16x8 af[2][MT], bfr[2][2];
         auto load_frags = [&](int j, int h) {
             const char* sa = smem + (j % NSTAGE_A) * OPER_BYTES;
             const char* sb = smem + LDS_B_BASE + (j % NSTAGE_B) * OPER_BYTES;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-                    af[s][mt] = A_KC ? lds_frag_kc(sa, wm * 128 + mt * 32, 2 * h + s, lane)
-                                     : lds_frag_mnc(sa, wm * 128 + mt * 32, 2 * h + s, lane);
+                for (int mt = 0; mt < MT; ++mt)
+                    af[s][mt] = A_KC ? lds_frag_kc(sa, wm * WROWS + mt * 32, 2 * h + s, lane)
+                                     : lds_frag_mnc(sa, wm * WROWS + mt * 32, 2 * h + s, lane);
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
                     bfr[s][nt] = B_KC ? lds_frag_kc(sb, b_rowbase[nt], 2 * h + s, lane)
@@ -340,7 +352,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 #pragma unroll
             for (int s = 0; s < 2; ++s)
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
+                for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
                         // B fragment first: the accumulator then holds, per lane, one row m of
@@ -391,7 +403,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         if (wm == 0) phase_barrier();                     // balances group 1's extra barrier
     }
 
-    if (EPI == EPI_STORE_T) {
+    if constexpr (EPI == EPI_STORE_T) {
         // ---- transposed epilogue: out0[n][m] = C[m][n] ---------------------------------
         // With the A fragment first, acc[mt][nt][r] is C[row][col] with
         //   row = m0 + wm*128 + mt*32 + 8*(r/4) + 4*(lane/32) + r%4,  col = n0 + wn*64 + nt*32 + lane%32:
@@ -456,7 +468,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 
     // ---- epilogue --------------------------------------------------------------
     // With the B fragment as first MFMA operand, acc[mt][nt][r] is C[row][col] with
-    //   row = m0 + wm*128 + mt*32 + lane%32
+    //   row = m0 + wm*WROWS + mt*32 + lane%32        (WROWS = 128, or 64 in the 128-row variant)
     //   col = (tile column base) + nt*32 + 8*(r/4) + 4*(lane/32) + r%4
     // i.e. each register quad r = 4g..4g+3 is four consecutive columns of one row.
     // The tile leaves through LDS (free after the main loop): per pass mt, every
@@ -485,7 +497,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
             const int cid = tg + 256 * i;
             const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
-            const int row = m0 + wm * 128 + mt * 32 + r;
+            const int row = m0 + wm * WROWS + mt * 32 + r;
             const int col = n0 + c * 8;
             if (row >= Meff || col >= P.N) continue;
             const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
@@ -496,7 +508,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     prefetch_gu(0);
 
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < MT; ++mt) {
         char* sbuf = smem + ((mt & 1) * 2 + wm) * SLICE_BYTES;
         // ---- dump this wave's part of the slice
 #pragma unroll
@@ -512,13 +524,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                                           (lane & 31) * SLICE_STRIDE + col * 4) = v;
             }
         lds_barrier();
-        if (mt + 1 < 4) prefetch_gu(mt + 1);
+        if (mt + 1 < MT) prefetch_gu(mt + 1);
         // ---- row-contiguous chunks of 8 columns
 #pragma unroll
         for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
             const int cid = tg + 256 * i;
             const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
-            const int row = m0 + wm * 128 + mt * 32 + r;
+            const int row = m0 + wm * WROWS + mt * 32 + r;
             const int col = n0 + c * 8;
             if (row >= Meff || col >= P.N) continue;
             // lanes c >= 8 (mod 16) read their second half first: conflict-free 16-byte reads
@@ -624,7 +636,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 
 // One workgroup's share of a plain (optionally split-K, optionally batched) GEMM: `block` of
 // `nblocks` in the launch order of this problem.
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const int nblocks) {
     int tm, tn, z;
     tile_of_block(block, nblocks, P.tiles_m, P.tiles_n, tm, tn, z);
@@ -638,18 +650,18 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     }
     const int Meff = effective_rows(P.M, P.m_dev);
     const int Keff = effective_rows(P.K, P.k_dev);
-    if (tm * BM >= Meff) return;    // whole block leaves together: no barrier was reached yet
+    if (tm * (NARROW ? BM / 2 : BM) >= Meff) return;    // whole block leaves together: no barrier was reached yet
     const int ktotal = ((Keff + BK - 1) / BK) * P.pairs;
     const int per_split = (ktotal + P.splits - 1) / P.splits;
     const int kt_begin = z * per_split;
     int kt_end = kt_begin + per_split;
     if (kt_end > ktotal) kt_end = ktotal;
-    gemm_tile<A_KC, B_KC, EPI>(P, tm, tn, z, kt_begin, kt_end, Meff, Keff);
+    gemm_tile<A_KC, B_KC, EPI, NARROW>(P, tm, tn, z, kt_begin, kt_end, Meff, Keff);
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_kernel(GemmArgs P) {
-    gemm_block<A_KC, B_KC, EPI>(P, (int)blockIdx.x, (int)gridDim.x);
+    gemm_block<A_KC, B_KC, EPI, NARROW>(P, (int)blockIdx.x, (int)gridDim.x);
 }
 
 // Two independent GEMMs in one grid: workgroups [0, nblocks0) run problem 0 (launched

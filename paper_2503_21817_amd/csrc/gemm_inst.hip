@@ -3,9 +3,9 @@
 
 namespace skipffn {
 
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 static hipError_t set_lds_limit() {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<A_KC, B_KC, EPI>),
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<A_KC, B_KC, EPI, NARROW>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
 }
 
@@ -15,6 +15,9 @@ hipError_t gemm_init() {
     if ((e = set_lds_limit<true, true, EPI_PARTIAL>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_STORE>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_SWIGLU, true>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_PARTIAL, true>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER, true>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_STORE_T>()) != hipSuccess) return e;
@@ -34,16 +37,17 @@ hipError_t gemm_init() {
     return hipSuccess;
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     const unsigned blocks = (unsigned)(a.tiles_m * a.tiles_n * a.splits * a.batch);
-    hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI>), dim3(blocks), dim3(GEMM_THREADS),
+    hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI, NARROW>), dim3(blocks), dim3(GEMM_THREADS),
                        GEMM_LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
 static void finish_args(int epi, GemmArgs& a) {
-    a.tiles_m = (a.M + BM - 1) / BM;
+    const int tm_rows = a.narrow ? BM / 2 : BM;
+    a.tiles_m = (a.M + tm_rows - 1) / tm_rows;
     a.tiles_n = (epi == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     if (a.splits < 1) a.splits = 1;
     if (a.batch < 1) a.batch = 1;
@@ -96,6 +100,12 @@ hipError_t launch_gemm_selfsim(const bf16_t* xn, int C, const SegTable& st, int 
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s) {
     finish_args(epi, a);
     if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
+    if (a.narrow) {
+        if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU, true>(a, s);
+        if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL, true>(a, s);
+        if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER, true>(a, s);
+        return hipErrorInvalidValue;
+    }
     if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU>(a, s);
     if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL>(a, s);
     if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER>(a, s);

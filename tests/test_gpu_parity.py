@@ -431,3 +431,39 @@ def test_smallest_and_widest_shapes(w):
         assert rel_l2(t.double().cpu().numpy(), bo[k]) < REL_L2_TOL, k
     assert rel_l2(dgain.double().cpu().numpy(), bo["dgain"]) < REL_L2_TOL
 
+
+
+@pytest.mark.parametrize("R", [1, 63, 64, 65, 127, 128, 129, 191, 255, 256, 257])
+@pytest.mark.parametrize("r_host", [True, False], ids=["R-host", "R-device"])
+def test_row_counts_around_the_128_row_tiles(R, r_host):
+    """Up to 256 retained rows the forward GEMMs run on 128-row tiles (one or two rows of tiles,
+    split-K partial sums for the down projection); 257 is the first count on 256-row tiles.
+    With the count on the device the row bound is T, which selects the tile height."""
+    visual = R - 7 if R > 7 else R
+    text = R - visual
+    T_pad = 40 if r_host else 0          # R-device: keep T (the bound) within the 128-row variant too
+    w = W.small(C=520, I=1368, visual=(visual + T_pad,), text=(text,), keep=(visual,), seed=300 + R,
+                name=f"rows-{R}")
+    assert w.R == R
+    print(f"narrow tiles R={R} T={w.T} r_host={r_host}", flush=True)
+    p = Problem(w, unit_gain=False, with_gain_tensor=True)
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps)
+    fo_nr = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps, no_residual=True)
+    idx, sk = fo["idx"], p.mask != 0
+    for saved in (False, True):
+        out, bufs = gpu_forward(p, R_host=r_host, saved=saved, flags=B.FLAG_NO_RESIDUAL)
+        got = bits_of(out)
+        assert np.array_equal(got[sk], p.hidden[sk])
+        assert rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo_nr["out_bits"][idx])) < REL_L2_TOL
+        out, bufs = gpu_forward(p, R_host=r_host, saved=saved, inplace=True)
+        got = bits_of(out)
+        assert np.array_equal(got[sk], p.hidden[sk])
+        assert rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx])) < REL_L2_TOL
+    sv = bufs.saved_views(R)
+    for k in ("G", "U", "H"):
+        assert rel_l2(f64_of(sv[k]), fo[k]) < REL_L2_TOL, k
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    gh, dw = gpu_backward(p, bufs, R_host=r_host)
+    assert rel_l2(O.bf16_bits_to_f64(bits_of(gh)[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
+    for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+        assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, k
