@@ -40,6 +40,7 @@ hipError_t ensure_gemm_init() {
 }
 
 constexpr int kMaxSplits = 8;
+constexpr int kMaxSplitsNarrow = 16;     // few rows: small fp32 slabs, and every CU has to stream weights
 
 // How the K range of a GEMM with tiles_m x tiles_n output tiles and `ktiles` K slabs is cut
 // on 256 CUs (one workgroup per CU).  Costs are in units of one K slab of one tile: every
@@ -91,7 +92,7 @@ KPartition choose_k_split_narrow(int tiles_m, int tiles_n, int ktiles) {
     const int tiles = tiles_m * tiles_n;
     KPartition best{1, 0};
     double best_cost = 1e30;
-    for (int s = 1; s <= kMaxSplits; ++s) {
+    for (int s = 1; s <= kMaxSplitsNarrow; ++s) {
         const int per = (ktiles + s - 1) / s;
         if (s > 1 && per < 8) break;
         const int rounds = (tiles * s + 255) / 256;
@@ -124,7 +125,7 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     w.xn = o;   if (!has_saved) o += align_up((size_t)R * C * 2);
     w.rstd = o; if (!has_saved) o += align_up((size_t)R * 4);
     w.h = o;    if (!has_saved) o += align_up((size_t)R * I * 2);
-    w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
+    w.partial = o; o += align_up((size_t)(narrow_rows(R) ? kMaxSplitsNarrow : kMaxSplits) * R * C * 4);
     w.total = o;
     return w;
 }
