@@ -125,7 +125,10 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     w.xn = o;   if (!has_saved) o += align_up((size_t)R * C * 2);
     w.rstd = o; if (!has_saved) o += align_up((size_t)R * 4);
     w.h = o;    if (!has_saved) o += align_up((size_t)R * I * 2);
-    w.partial = o; o += align_up((size_t)(narrow_rows(R) ? kMaxSplitsNarrow : kMaxSplits) * R * C * 4);
+    // a buffer sized for R_max rows must do for every smaller count: the 128-row variant (up to
+    // 256 rows) may use more slabs than the 256-row tiles
+    const size_t slab_rows = std::max<size_t>((size_t)kMaxSplits * R, (size_t)kMaxSplitsNarrow * std::min<int64_t>(R, 256));
+    w.partial = o; o += align_up(slab_rows * C * 4);
     w.total = o;
     return w;
 }

@@ -225,3 +225,16 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         B.lib()
+
+
+def test_buffer_sizes_grow_with_the_row_bound():
+    """A buffer sized for R_max rows is accepted for every smaller row count: the size queries
+    never decrease as R_max grows (the tile variant and the K split change with the row count)."""
+    lib = B.lib()
+    C, I = 4096, 14336
+    prev = (0, 0, 0, 0)
+    for R in list(range(0, 600)) + [1000, 1472, 4096, 16384]:
+        cur = (lib.skipffn_forward_workspace_bytes(R, C, I, 0), lib.skipffn_forward_workspace_bytes(R, C, I, 1),
+               lib.skipffn_backward_workspace_bytes(R, C, I), lib.skipffn_saved_bytes(R, C, I))
+        assert all(c >= p for c, p in zip(cur, prev)), (R, cur, prev)
+        prev = cur

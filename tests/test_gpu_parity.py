@@ -467,3 +467,30 @@ def test_row_counts_around_the_128_row_tiles(R, r_host):
     assert rel_l2(O.bf16_bits_to_f64(bits_of(gh)[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
     for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
         assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, k
+
+
+@pytest.mark.parametrize("R_max", [300, 2000])
+def test_buffers_sized_for_a_larger_row_bound(R_max):
+    """Buffers sized once for R_max rows serve a call with fewer rows (here a count that takes the
+    128-row tiles and more K splits than the bound's own configuration would)."""
+    w = W.small(C=520, I=1368, visual=(200,), text=(13,), keep=(87,), seed=55, name="bound")
+    p = Problem(w)
+    bufs = B.SkipFFNBuffers(w.T, R_max, w.C, w.I, training=True)
+    B.skipffn_compact(p.d_mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+    out = p.d_hidden.clone()
+    B.skipffn_forward(out, out, bufs.idx, w.R, p.d_wg, p.d_wu, p.d_wd, eps=w.eps, saved=bufs.saved,
+                      workspace=bufs.fwd_ws)
+    gh = p.d_grad.clone()
+    dw = [torch.empty((w.I, w.C), dtype=torch.bfloat16, device="cuda"),
+          torch.empty((w.I, w.C), dtype=torch.bfloat16, device="cuda"),
+          torch.empty((w.C, w.I), dtype=torch.bfloat16, device="cuda")]
+    B.skipffn_backward(gh, gh, bufs.idx, w.R, p.d_wg, p.d_wu, p.d_wd, bufs.saved, *dw, eps=w.eps,
+                       workspace=bufs.bwd_ws)
+    torch.cuda.synchronize()
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, None, w.eps)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, None, w.eps)
+    idx = fo["idx"]
+    assert rel_l2(O.bf16_bits_to_f64(bits_of(out)[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx])) < REL_L2_TOL
+    assert rel_l2(O.bf16_bits_to_f64(bits_of(gh)[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
+    for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+        assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, k
