@@ -186,6 +186,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     constexpr int WROWS = TM / 2;                   // rows per wave row group
     constexpr int MT = WROWS / 32;                  // MFMA tiles per wave along M
     constexpr int A_LOADS = TM / 64;                // 1 KB regions of an A slab each wave fills
+    // The A ring: 2 stages of 32 KB, fetched one slab ahead - or, for the 128-row tile, 3 stages
+    // of 16 KB fetched two slabs ahead, in the same phase as B.  The 128-row tile streams its B
+    // operand from HBM (few or no other tiles of the grid share it in L2); issuing everything in
+    // the first phase of slab j lets a load stay in flight for 2 slab times instead of 1 (A) and
+    // 1.4 (B): measured 4-6 % faster on the gate/up GEMM up to 256 rows.
+    constexpr int NSA = NARROW ? 3 : NSTAGE_A;
+    constexpr int A_STAGE = NARROW ? OPER_BYTES / 2 : OPER_BYTES;
+    constexpr int A_AHEAD = NARROW ? 2 : 1;
+    constexpr int B_BASE = NSA * A_STAGE;
+    static_assert(B_BASE + NSTAGE_B * OPER_BYTES <= GEMM_LDS_BYTES, "operand rings must fit in LDS");
     extern __shared__ __align__(16) char smem[];
     const int t = threadIdx.x;
     const int lane = t & 63;
@@ -258,7 +268,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         const int pair = kt >= ktiles_pair ? 1 : 0;
         const int kg = (kt - pair * ktiles_pair) * BK;  // k offset inside the pair
         __amdgpu_buffer_rsrc_t src = pair ? rA1 : rA0;
-        char* dst = smem + (j % NSTAGE_A) * OPER_BYTES + wave * (A_LOADS * 1024) + i * 1024;
+        char* dst = smem + (j % NSA) * A_STAGE + wave * (A_LOADS * 1024) + i * 1024;
         const uint32_t step = A_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.lda) * 2);
         if (SCALAR_STEP && kg + BK <= Keff) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)a_goff[i], (int)step, 0, 0);
@@ -274,7 +284,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         const int kg = (kt - pair * ktiles_pair) * BK;
         __amdgpu_buffer_rsrc_t src = pair ? rB1 : rB0;
         if (EPI == EPI_SWIGLU) src = wave >= 4 ? rB1 : rB0;   // regions 16.. = rows 128..
-        char* dst = smem + LDS_B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096 + i * 1024;
+        char* dst = smem + B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096 + i * 1024;
         const uint32_t step = B_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.ldb) * 2);
         if (SCALAR_STEP && kg + BK <= Keff) {
             __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)b_goff[i], (int)step, 0, 0);
@@ -333,8 +343,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         // flight, so A(j+1) and B(j+1) are visible to all waves from phase p+4 on.
         bf16x8 af[2][MT], bfr[2][2];
         auto load_frags = [&](int j, int h) {
-            const char* sa = smem + (j % NSTAGE_A) * OPER_BYTES;
-            const char* sb = smem + LDS_B_BASE + (j % NSTAGE_B) * OPER_BYTES;
+            const char* sa = smem + (j % NSA) * A_STAGE;
+            const char* sb = smem + B_BASE + (j % NSTAGE_B) * OPER_BYTES;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
 #pragma unroll
@@ -368,22 +378,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
         };
-        // slab j+1 of both operands has landed; B(j+2), if it was issued, may still fly
+        // slab j+1 of both operands has landed; what slab j issued for slab j+2 (B, and A when it
+        // is fetched two ahead) may still fly
+        constexpr int FLYING = 4 + (A_AHEAD == 2 ? A_LOADS : 0);
         auto wait_next_slab = [&](int j) {
-            if (j + 2 < nk) SKIPFFN_WAIT_VMCNT(4); else SKIPFFN_WAIT_VMCNT(0);
+            if (j + 2 < nk) SKIPFFN_WAIT_VMCNT(FLYING); else SKIPFFN_WAIT_VMCNT(0);
         };
 
-        // prologue: A(0), B(0), B(1) issued; A(0) and B(0) landed and visible
+        // prologue: slabs 0 and 1 issued (A(1) only when A is fetched two ahead); A(0) and B(0)
+        // landed and visible
         gload_a(0);
         gload_b(0);
-        if (nk > 1) { gload_b(1); SKIPFFN_WAIT_VMCNT(4); } else { SKIPFFN_WAIT_VMCNT(0); }
+        if (nk > 1) {
+            if (A_AHEAD == 2) gload_a(1);
+            gload_b(1);
+            SKIPFFN_WAIT_VMCNT(FLYING);
+        } else {
+            SKIPFFN_WAIT_VMCNT(0);
+        }
         phase_barrier();
         if (wm == 1) phase_barrier();                     // group 1 starts one phase later
 
         for (int j = 0; j < nk; ++j) {
             // M(j,0)
             load_frags(j, 0);
-            if (j + 1 < nk) gload_a(j + 1);
+            if (j + A_AHEAD < nk) gload_a(j + A_AHEAD);
+            if (NARROW && j + 2 < nk) gload_b(j + 2);
             SKIPFFN_WAIT_LGKMCNT0();
             phase_barrier();
             // C(j,0)
@@ -391,7 +411,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             phase_barrier();
             // M(j,1)
             load_frags(j, 1);
-            if (j + 2 < nk) gload_b(j + 2);
+            if (!NARROW && j + 2 < nk) gload_b(j + 2);
             if (wm == 1) wait_next_slab(j);
             SKIPFFN_WAIT_LGKMCNT0();
             phase_barrier();
