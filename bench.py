@@ -406,30 +406,33 @@ def merge_sweep(torch, B, args):
             "config": {"workload": "1024 -> 256 tokens per set"}, "sweep": rows}
 
 
-def mfma_sweep(torch, B, args):
-    """What the matrix cores of this box sustain with operands in registers (no memory traffic):
-    constant operands, then pseudo-random bf16 operands.  2 workgroups of 4 wavefronts per CU."""
-    blocks, iters = 512, 20000
+def mfma_probe(torch, B, random_operands, iters, steps, warmup, blocks=512):
+    """One figure of the register-only MFMA loop: 2 workgroups of 4 wavefronts per CU, operands in
+    registers, no memory traffic."""
     out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
     clocks = torch.zeros(2 * blocks, dtype=torch.int64, device="cuda")
-    rows = []
-    for random_operands in (0, 1):
-        for _ in range(max(args.warmup, 1)):
-            B.skipffn_probe_mfma(blocks, iters, random_operands, out, clocks)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
-            B.skipffn_probe_mfma(blocks, iters, random_operands, out, clocks)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / args.steps
-        flops = blocks * 4 * iters * 8 * 32768.0
-        c = clocks.view(blocks, 2).double()
-        ghz = float((c[:, 0].sum() / c[:, 1].sum()).item()) * 0.1       # cycles per 10 ns tick
-        rows.append({"operands": "random bf16" if random_operands else "constant 1.0",
-                     "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
-                     "frac_published_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                     "shader_clock_ghz": round(ghz, 3)})
+    for _ in range(max(warmup, 1)):
+        B.skipffn_probe_mfma(blocks, iters, random_operands, out, clocks)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        B.skipffn_probe_mfma(blocks, iters, random_operands, out, clocks)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    flops = blocks * 4 * iters * 8 * 32768.0
+    c = clocks.view(blocks, 2).double()
+    ghz = float((c[:, 0].sum() / c[:, 1].sum()).item()) * 0.1       # cycles per 10 ns tick
+    return {"operands": "random bf16" if random_operands else "constant 1.0",
+            "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+            "frac_published_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "shader_clock_ghz": round(ghz, 3)}
+
+
+def mfma_sweep(torch, B, args):
+    """What the matrix cores of this box sustain with operands in registers (no memory traffic):
+    constant operands, then pseudo-random bf16 operands."""
+    rows = [mfma_probe(torch, B, r, 20000, args.steps, args.warmup) for r in (0, 1)]
     return {"metric": "register-only MFMA loop", "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
             "config": {"workload": "512 workgroups x 4 wavefronts x 160000 v_mfma_f32_32x32x16_bf16"},
@@ -671,7 +674,7 @@ def main():
     if kind == "mfma":
         # the ceiling of THIS box, measured right after the timed region while the chip is warm:
         # a register-only MFMA loop on random bf16 operands (no memory traffic at all)
-        live = mfma_sweep(torch, B, argparse.Namespace(steps=3, warmup=1))["sweep"][1]
+        live = mfma_probe(torch, B, 1, 8000, steps=3, warmup=1)
         roofline["measured_ceiling"] = live["tflops"]
         roofline["measured_ceiling_clock_ghz"] = live["shader_clock_ghz"]
         roofline["frac_of_measured_ceiling"] = round(achieved / live["tflops"], 4)
