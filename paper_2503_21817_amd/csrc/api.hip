@@ -453,7 +453,7 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     SavedLayout L = saved_layout(Rb, C, I);
     const char* sv = static_cast<const char*>(saved);
     const bf16_t* xrows = reinterpret_cast<const bf16_t*>(sv + L.off[0]);
-    const bf16_t* xn = reinterpret_cast<const bf16_t*>(sv + L.off[1]);
+    // L.off[1] (the normalised rows, row-major) is not read here: the weight-gradient GEMMs take the transposed copy
     const float* rstd = reinterpret_cast<const float*>(sv + L.off[2]);
     const bf16_t* G = reinterpret_cast<const bf16_t*>(sv + L.off[3]);
     const bf16_t* U = reinterpret_cast<const bf16_t*>(sv + L.off[4]);
