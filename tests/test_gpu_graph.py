@@ -2,7 +2,6 @@
 allocates nothing, never synchronises and uses only kernels (no memset nodes), so a caller may
 capture it.  Replays are interleaved with eager work and every replay is compared with the
 eager result."""
-import numpy as np
 import pytest
 import torch
 
