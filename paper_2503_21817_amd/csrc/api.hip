@@ -102,6 +102,29 @@ KPartition choose_k_split_narrow(int tiles_m, int tiles_n, int ktiles) {
     return best;
 }
 
+// Gate/up GEMM with few rows: one row of tiles has only I / 128 workgroups (112 for I = 14336), and a
+// workgroup cannot keep enough weight bytes in flight to make up for the idle CUs.  Up to 128 rows
+// the K range is therefore split over 2..4 workgroups per tile, which write fp32 partial sums of
+// gate and up; the SwiGLU moves to the reducing kernel.  0 = not used (fused epilogue instead).
+// Measured at C=4096, I=14336 (GEMM + reduction against the fused 128-row GEMM): 53 / 72 us at 16
+// rows, 57 / 71 at 64, 65 / 73 at 128; at 184 and 256 rows the partial sums (229 KB per row, written
+// and read) cost what the split gains.
+constexpr int64_t kGateUpSplitMaxRows = BM / 2;
+inline int gate_up_splits(int64_t rows, int64_t C, int64_t I) {
+    if (rows > kGateUpSplitMaxRows) return 0;
+    const int64_t tiles_n = (I + BN / 2 - 1) / (BN / 2), ktiles = (C + BK - 1) / BK;
+    int64_t s = std::min<int64_t>(4, 256 / std::max<int64_t>(tiles_n, 1));
+    while (s > 1 && ktiles / s < 8) --s;
+    return s >= 2 ? (int)s : 0;
+}
+inline size_t gate_up_partial_bytes(int64_t R, int64_t C, int64_t I) {
+    // sized for the largest row count that takes this path, so that a bound covers every smaller count
+    const int64_t rows = std::min<int64_t>(R, kGateUpSplitMaxRows);
+    const int s = gate_up_splits(rows, C, I);
+    const int64_t tiles_n = (I + BN / 2 - 1) / (BN / 2);
+    return s ? (size_t)s * (size_t)rows * (size_t)tiles_n * BN * 4 : 0;
+}
+
 inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
 
 struct SavedLayout { size_t off[7]; size_t total; };
@@ -119,7 +142,7 @@ SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
     return L;
 }
 
-struct FwdWs { size_t xn, rstd, h, partial, total; };
+struct FwdWs { size_t xn, rstd, h, partial, gu_partial, total; };
 FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     FwdWs w; size_t o = 0;
     w.xn = o;   if (!has_saved) o += align_up((size_t)R * C * 2);
@@ -129,6 +152,7 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     // 256 rows) may use more slabs than the 256-row tiles
     const size_t slab_rows = std::max<size_t>((size_t)kMaxSplits * R, (size_t)kMaxSplitsNarrow * std::min<int64_t>(R, 256));
     w.partial = o; o += align_up(slab_rows * C * 4);
+    w.gu_partial = o; o += align_up(gate_up_partial_bytes(R, C, I));
     w.total = o;
     return w;
 }
@@ -356,10 +380,21 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         a.B0 = static_cast<const bf16_t*>(w_gate); a.B1 = static_cast<const bf16_t*>(w_up);
         a.ldb = (int)C; a.b_bytes = (uint32_t)(I * C * 2);
         a.pairs = 1; a.splits = 1;
-        a.narrow = narrow_rows(Rb) ? 1 : 0;
         a.out0 = H; a.out1 = G; a.out2 = U; a.ldo = (int)I;
+        const int gu_splits = gate_up_splits(Rb, C, I);
         profile_mark_begin(KC_GEMM_GATE_UP, s);
-        e = launch_gemm(true, true, EPI_SWIGLU, a, s);
+        if (gu_splits) {
+            // few rows: split K on 128-row tiles, fp32 partial sums, SwiGLU in the reducing kernel
+            a.narrow = 1;
+            a.splits = gu_splits;
+            a.partial = reinterpret_cast<float*>(ws + W.gu_partial);
+            e = launch_gemm(true, true, EPI_PARTIAL_GU, a, s);
+            if (e == hipSuccess)
+                e = launch_swiglu_reduce(a.partial, gu_splits, (int)Rb, r_dev, (int)I, a.tiles_n * BN, H, G, U, s);
+        } else {
+            a.narrow = narrow_rows(Rb) ? 1 : 0;
+            e = launch_gemm(true, true, EPI_SWIGLU, a, s);
+        }
         profile_mark_end(KC_GEMM_GATE_UP, s);
         if (e != hipSuccess) return hip_fail(e);
     }

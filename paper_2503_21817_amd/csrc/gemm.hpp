@@ -48,7 +48,9 @@ enum EpiKind : int {
     EPI_PARTIAL = 2,       // fp32 partial[z][M][N]
     EPI_RESID_SCATTER = 3, // out0[idx[m]][n] = bf16(res[idx[m]][n] + acc)
     EPI_SWIGLU_BWD = 4,    // acc = dH; e0=G, e1=U -> out0 = dG, out1 = dU (bf16)
-    EPI_STORE_T = 5        // like EPI_STORE, but the result is written transposed: out0[n][m] (ldo = M extent)
+    EPI_STORE_T = 5,       // like EPI_STORE, but the result is written transposed: out0[n][m] (ldo = M extent)
+    EPI_PARTIAL_GU = 6     // B as for EPI_SWIGLU, fp32 partial[z][M][tiles_n * 256]: tile tn owns columns
+                           // tn*256 .. +127 (gate) and +128 .. +255 (up); the SwiGLU is applied by the reducing kernel
 };
 
 struct GemmArgs {
@@ -186,6 +188,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     constexpr int WROWS = TM / 2;                   // rows per wave row group
     constexpr int MT = WROWS / 32;                  // MFMA tiles per wave along M
     constexpr int A_LOADS = TM / 64;                // 1 KB regions of an A slab each wave fills
+    constexpr bool GU = (EPI == EPI_SWIGLU || EPI == EPI_PARTIAL_GU);   // B tile = 128 rows of W_gate + 128 of W_up
     // The A ring: 2 stages of 32 KB, fetched one slab ahead - or, for the 128-row tile, 3 stages
     // of 16 KB fetched two slabs ahead, in the same phase as B.  The 128-row tile streams its B
     // operand from HBM (few or no other tiles of the grid share it in L2); issuing everything in
@@ -204,7 +207,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     const int wn = wave & 3;       // 0..3
 
     const int m0 = tm * TM;
-    const int n0 = (EPI == EPI_SWIGLU) ? tn * (BN / 2) : tn * BN;
+    const int n0 = GU ? tn * (BN / 2) : tn * BN;
     const int ktiles_pair = (Keff + BK - 1) / BK;
     const int nk = kt_end > kt_begin ? kt_end - kt_begin : 0;
 
@@ -242,7 +245,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         if (B_KC) {
             int row = 8 * q + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
             // SWIGLU: tile rows 0..127 are W_gate rows, 128..255 the same rows of W_up
-            int gr = (EPI == EPI_SWIGLU) ? n0 + (row & 127) : n0 + row;
+            int gr = GU ? n0 + (row & 127) : n0 + row;
             b_goff[i] = gr < P.N ? (uint32_t)(((int64_t)gr * P.ldb + c * 8) * 2) : kOobOffset;
             b_kk[i] = c * 8;
         } else {
@@ -283,7 +286,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         const int pair = kt >= ktiles_pair ? 1 : 0;
         const int kg = (kt - pair * ktiles_pair) * BK;
         __amdgpu_buffer_rsrc_t src = pair ? rB1 : rB0;
-        if (EPI == EPI_SWIGLU) src = wave >= 4 ? rB1 : rB0;   // regions 16.. = rows 128..
+        if (GU) src = wave >= 4 ? rB1 : rB0;   // regions 16.. = rows 128..
         char* dst = smem + B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096 + i * 1024;
         const uint32_t step = B_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.ldb) * 2);
         if (SCALAR_STEP && kg + BK <= Keff) {
@@ -313,7 +316,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 
     // rows of the B tile read by this wave's two n-tiles
     int b_rowbase[2];
-    if (EPI == EPI_SWIGLU) {
+    if (GU) {
         b_rowbase[0] = wn * 32;          // gate columns
         b_rowbase[1] = 128 + wn * 32;    // the same columns of up
     } else {
@@ -538,8 +541,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                 f32x4 v = {acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2],
                            acc[mt][nt][4 * g + 3]};
                 int col, mat;
-                if (EPI == EPI_SWIGLU) { mat = nt; col = wn * 32 + 8 * g + 4 * h; }
-                else                   { mat = 0;  col = wn * 64 + nt * 32 + 8 * g + 4 * h; }
+                if (EPI == EPI_SWIGLU)          { mat = nt; col = wn * 32 + 8 * g + 4 * h; }
+                else if (EPI == EPI_PARTIAL_GU) { mat = 0;  col = nt * 128 + wn * 32 + 8 * g + 4 * h; }
+                else                            { mat = 0;  col = wn * 64 + nt * 32 + 8 * g + 4 * h; }
                 *reinterpret_cast<f32x4*>(sbuf + mat * EPI_ROWS * SLICE_STRIDE +
                                           (lane & 31) * SLICE_STRIDE + col * 4) = v;
             }
@@ -552,7 +556,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
             const int row = m0 + wm * WROWS + mt * 32 + r;
             const int col = n0 + c * 8;
-            if (row >= Meff || col >= P.N) continue;
+            if (row >= Meff || (EPI != EPI_PARTIAL_GU && col >= P.N)) continue;
             // lanes c >= 8 (mod 16) read their second half first: conflict-free 16-byte reads
             const int swap = (c >> 3) & 1;
             float v[8], w[8];
@@ -608,6 +612,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                     for (int k = 0; k < 4; ++k) pk[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
                     *O = pk;
                 }
+            } else if (EPI == EPI_PARTIAL_GU) {
+                // every column of the tile is written (rows of W beyond N read as zeros)
+                f32x4* O = reinterpret_cast<f32x4*>(P.partial + ((int64_t)z * P.M + row) * ((int64_t)P.tiles_n * BN) +
+                                                    (int64_t)tn * BN + c * 8);
+                f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};
+                O[0] = lo;
+                O[1] = hi;
             } else if (EPI == EPI_PARTIAL) {
                 f32x4* O = reinterpret_cast<f32x4*>(P.partial + ((int64_t)z * P.M + row) * P.N + col);
                 f32x4 lo = {v[0], v[1], v[2], v[3]}, hi = {v[4], v[5], v[6], v[7]};

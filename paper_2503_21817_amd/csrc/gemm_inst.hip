@@ -18,6 +18,8 @@ hipError_t gemm_init() {
     if ((e = set_lds_limit<true, true, EPI_SWIGLU, true>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_PARTIAL, true>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER, true>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_PARTIAL_GU, true>()) != hipSuccess) return e;
+    if ((e = set_lds_limit<true, true, EPI_PARTIAL_GU>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_STORE_T>()) != hipSuccess) return e;
@@ -48,7 +50,7 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
 static void finish_args(int epi, GemmArgs& a) {
     const int tm_rows = a.narrow ? BM / 2 : BM;
     a.tiles_m = (a.M + tm_rows - 1) / tm_rows;
-    a.tiles_n = (epi == EPI_SWIGLU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
+    a.tiles_n = (epi == EPI_SWIGLU || epi == EPI_PARTIAL_GU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     if (a.splits < 1) a.splits = 1;
     if (a.batch < 1) a.batch = 1;
 }
@@ -104,10 +106,12 @@ hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s
         if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU, true>(a, s);
         if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL, true>(a, s);
         if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER, true>(a, s);
+        if (a_kc && b_kc && epi == EPI_PARTIAL_GU) return launch_one<true, true, EPI_PARTIAL_GU, true>(a, s);
         return hipErrorInvalidValue;
     }
     if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU>(a, s);
     if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL>(a, s);
+    if (a_kc && b_kc && epi == EPI_PARTIAL_GU) return launch_one<true, true, EPI_PARTIAL_GU>(a, s);
     if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER>(a, s);
     if (a_kc && b_kc && epi == EPI_STORE) return launch_one<true, true, EPI_STORE>(a, s);
     if (a_kc && !b_kc && epi == EPI_SWIGLU_BWD) return launch_one<true, false, EPI_SWIGLU_BWD>(a, s);

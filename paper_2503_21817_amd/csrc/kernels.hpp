@@ -53,6 +53,9 @@ struct PartialLayout { int splits; int sk_nbg; int sk_kt; };
 hipError_t launch_resid_scatter(const float* partial, PartialLayout pl, int R, const int32_t* r_dev,
                                 int C, const int32_t* idx, const bf16_t* res, bf16_t* out,
                                 int no_residual, hipStream_t s);
+// SwiGLU over the split-K partial sums of a gate/up GEMM run with EPI_PARTIAL_GU (ldp = tiles_n * 256)
+hipError_t launch_swiglu_reduce(const float* partial, int splits, int R, const int32_t* r_dev, int I, int ldp,
+                                bf16_t* H, bf16_t* G, bf16_t* U, hipStream_t s);
 // dst[r] = src[idx[r]]  (rows of row_bytes, multiple of 16)
 hipError_t launch_gather_rows(const void* src, void* dst, int64_t row_bytes, const int32_t* idx,
                               int R, const int32_t* r_dev, hipStream_t s);

@@ -176,6 +176,55 @@ hipError_t launch_resid_scatter(const float* partial, PartialLayout pl, int R, c
     return hipGetLastError();
 }
 
+// ---- SwiGLU over split-K partial sums of the gate/up GEMM (few rows) ------------------------------
+// partial[z][Rbound][ldp] fp32, ldp = tiles_n * 256: tile tn holds gate columns tn*128 .. +127 at
+// tn*256 and the same up columns at tn*256 + 128.  One thread per 8 columns of I:
+// H = silu(sum_z gate) * sum_z up (and G, U when they are saved), splits summed in order.
+__global__ __launch_bounds__(ROW_THREADS) void swiglu_reduce_kernel(
+    const float* __restrict__ partial, int splits, int Rbound, const int32_t* __restrict__ r_dev, int I,
+    int ldp, bf16_t* __restrict__ H, bf16_t* __restrict__ G, bf16_t* __restrict__ U) {
+    const int R = effective_rows(Rbound, r_dev);
+    const int chunks = I >> 3;
+    const int64_t gid = (int64_t)blockIdx.x * ROW_THREADS + threadIdx.x;
+    const int r = (int)(gid / chunks), c = (int)(gid - (int64_t)r * chunks);
+    if (r >= R) return;
+    const int i0 = c * 8;
+    const float* p = partial + (int64_t)r * ldp + (i0 >> 7) * 256 + (i0 & 127);
+    const int64_t zstride = (int64_t)Rbound * ldp;
+    float g[8], u[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { g[j] = 0.0f; u[j] = 0.0f; }
+    for (int z = 0; z < splits; ++z) {
+        const f32x4 g0 = *reinterpret_cast<const f32x4*>(p + z * zstride);
+        const f32x4 g1 = *reinterpret_cast<const f32x4*>(p + z * zstride + 4);
+        const f32x4 u0 = *reinterpret_cast<const f32x4*>(p + z * zstride + 128);
+        const f32x4 u1 = *reinterpret_cast<const f32x4*>(p + z * zstride + 132);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            g[j] += g0[j]; g[4 + j] += g1[j];
+            u[j] += u0[j]; u[4 + j] += u1[j];
+        }
+    }
+    float h[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j])) * u[j];
+    const int64_t o = (int64_t)r * I + i0;
+    *reinterpret_cast<u32x4*>(H + o) = pack8(h);
+    if (G != nullptr) {
+        *reinterpret_cast<u32x4*>(G + o) = pack8(g);
+        *reinterpret_cast<u32x4*>(U + o) = pack8(u);
+    }
+}
+
+hipError_t launch_swiglu_reduce(const float* partial, int splits, int R, const int32_t* r_dev, int I, int ldp,
+                                bf16_t* H, bf16_t* G, bf16_t* U, hipStream_t s) {
+    if (R <= 0) return hipSuccess;
+    const int64_t total = (int64_t)R * (I >> 3);
+    dim3 grid((unsigned)((total + ROW_THREADS - 1) / ROW_THREADS)), block(ROW_THREADS);
+    hipLaunchKernelGGL(swiglu_reduce_kernel, grid, block, 0, s, partial, splits, R, r_dev, I, ldp, H, G, U);
+    return hipGetLastError();
+}
+
 // ---- row gather (upstream gradient rows; skip KV-cache of Section 4.3) -----------------
 constexpr int ROWS_PER_BLOCK = ROW_THREADS / 64;   // copy kernels: one wavefront per row
 __global__ __launch_bounds__(ROW_THREADS) void gather_rows_kernel(
