@@ -213,7 +213,8 @@ def prefill_sweep(torch, B, args):
     ws = [(torch.randn(shape, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
           for shape in ((I, C), (I, C), (C, I))]
     rows = []
-    for name, nseq, V, Tx, keep in (("llava-b1", 1, 576, 40, 144), ("llava-b2", 2, 576, 40, 144),
+    for name, nseq, V, Tx, keep in (("llava-b1-keep64", 1, 576, 40, 64), ("llava-b1", 1, 576, 40, 144),
+                                    ("llava-b2", 2, 576, 40, 144),
                                     ("llava-b4", 4, 576, 40, 144), ("llava-b8", 8, 576, 40, 144),
                                     ("llava-hd-b1", 1, 2880, 64, 576)):
         T, R = nseq * (V + Tx), nseq * (keep + Tx)
