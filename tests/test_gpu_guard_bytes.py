@@ -42,6 +42,8 @@ SHAPES = [
     W.small(C=264, I=520, visual=(700,), text=(9,), keep=(600,), seed=12, name="odd-dims-3tiles"),
     W.small(C=1024, I=2048, visual=(64,), text=(1,), keep=(0,), seed=13, name="one-row"),
     W.small(C=2048, I=5632, visual=(1100, 900), text=(30, 41), keep=(513, 300), seed=14, name="mid"),
+    W.small(C=2048, I=2816, visual=(200,), text=(9,), keep=(100,), seed=15, name="few-rows-split-gate-up"),
+    W.small(C=1024, I=1368, visual=(300,), text=(20,), keep=(180,), seed=16, name="two-128-row-tiles"),
 ]
 FLAGS = [0, B.FLAG_BALANCED_SPLIT, B.FLAG_DW_FP32 | B.FLAG_BALANCED_SPLIT]
 

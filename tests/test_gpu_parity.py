@@ -435,14 +435,19 @@ def test_smallest_and_widest_shapes(w):
 
 @pytest.mark.parametrize("R", [1, 63, 64, 65, 127, 128, 129, 191, 255, 256, 257])
 @pytest.mark.parametrize("r_host", [True, False], ids=["R-host", "R-device"])
-def test_row_counts_around_the_128_row_tiles(R, r_host):
+@pytest.mark.parametrize("C,I", [(520, 1368), (1024, 1368), (2048, 2816)],
+                         ids=["fused-gate-up", "gate-up-2-splits", "gate-up-4-splits"])
+def test_row_counts_around_the_128_row_tiles(R, r_host, C, I):
     """Up to 256 retained rows the forward GEMMs run on 128-row tiles (one or two rows of tiles,
-    split-K partial sums for the down projection); 257 is the first count on 256-row tiles.
-    With the count on the device the row bound is T, which selects the tile height."""
+    split-K partial sums for the down projection); 257 is the first count on 256-row tiles.  Up
+    to 128 rows the gate/up GEMM is split along K as well when K is long enough (C = 520 is not:
+    fused epilogue; C = 1024 gives 2 splits, C = 2048 with 22 column tiles 4) and the SwiGLU runs
+    in the reducing kernel.  With the count on the device the row bound is T, which selects the
+    variant."""
     visual = R - 7 if R > 7 else R
     text = R - visual
-    T_pad = 40 if r_host else 0          # R-device: keep T (the bound) within the 128-row variant too
-    w = W.small(C=520, I=1368, visual=(visual + T_pad,), text=(text,), keep=(visual,), seed=300 + R,
+    T_pad = 40 if r_host else 0          # R-device: keep T (the bound) within the same variant
+    w = W.small(C=C, I=I, visual=(visual + T_pad,), text=(text,), keep=(visual,), seed=300 + R,
                 name=f"rows-{R}")
     assert w.R == R
     print(f"narrow tiles R={R} T={w.T} r_host={r_host}", flush=True)
