@@ -157,3 +157,31 @@ def test_cfg5_32_stacked_layers():
                 assert e < REL_L2_TOL, (l, k, e)
     torch.cuda.synchronize()
     assert np.array_equal(bits_of(g)[sk], grad_top[sk])
+
+
+@pytest.mark.timeout(300)
+@pytest.mark.parametrize("keep", [64, 144], ids=["104-rows-split-gate-up", "184-rows-two-128-row-tiles"])
+def test_batch1_prefill_full_width(keep):
+    """One LLaVA-shaped sequence (576 visual + 40 text tokens) at the backbone's width, forward only
+    with nothing saved, as `bench.py --sweep prefill` times it: the few-row variants of both GEMMs
+    (128-row tiles; below 129 rows also the K split of gate/up with the SwiGLU in the reducing
+    kernel; 16 K splits in the down projection)."""
+    w = W.small(C=4096, I=14336, visual=(576,), text=(40,), keep=(keep,), seed=4100 + keep,
+                name=f"llava-b1-keep{keep}")
+    print(f"prefill {w.name}: T={w.T} R={w.R}", flush=True)
+    p = Problem(w)
+    bufs = B.SkipFFNBuffers(w.T, w.R, w.C, w.I, training=False)
+    hidden = p.d_hidden.clone()
+    B.skipffn_compact(p.d_mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+    B.skipffn_forward(hidden, hidden, bufs.idx, w.R, p.d_wg, p.d_wu, p.d_wd, eps=w.eps, workspace=bufs.fwd_ws)
+    torch.cuda.synchronize()
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, None, w.eps)
+    idx, sk = fo["idx"], p.mask != 0
+    out = bits_of(hidden)
+    assert np.array_equal(out[sk], p.hidden[sk])
+    want = O.bf16_bits_to_f64(fo["out_bits"][idx])
+    d = O.bf16_bits_to_f64(out[idx]) - want
+    e = float(np.linalg.norm(d) / np.linalg.norm(want))
+    print(f"  out rel-L2 {e:.3e}", flush=True)
+    assert e < REL_L2_TOL
+    assert (np.linalg.norm(d, axis=1) / np.linalg.norm(want, axis=1)).max() < REL_L2_TOL
