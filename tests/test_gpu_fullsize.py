@@ -185,3 +185,32 @@ def test_batch1_prefill_full_width(keep):
     print(f"  out rel-L2 {e:.3e}", flush=True)
     assert e < REL_L2_TOL
     assert (np.linalg.norm(d, axis=1) / np.linalg.norm(want, axis=1)).max() < REL_L2_TOL
+
+
+@pytest.mark.parametrize("which", ["cfg2", "cfg4-ragged", "llava-b1-keep64"])
+def test_repeated_steps_give_the_same_bits(which):
+    """Every reduction in the path has a fixed order (split-K slabs are summed by index, the
+    balanced split recomputes its plan, weight gradients are written by one workgroup per tile),
+    so repeating a step on the same inputs must reproduce every output bit for bit.  A race in the
+    LDS staging or in the operand rings would show up here as well."""
+    if which == "cfg2":
+        w = W.config(2)
+    elif which == "cfg4-ragged":
+        w = W.config(4)
+    else:
+        w = W.small(C=4096, I=14336, visual=(576,), text=(40,), keep=(64,), seed=4164, name=which)
+    print(f"determinism {w.name}: T={w.T} R={w.R}", flush=True)
+    p = Problem(w)
+    bufs = B.SkipFFNBuffers(w.T, w.R, w.C, w.I)
+    results = []
+    for rep in range(3):
+        hidden = p.d_hidden.clone()
+        grad = p.d_grad.clone()
+        dw = [torch.full((w.I, w.C), float("nan"), dtype=torch.bfloat16, device="cuda"),
+              torch.full((w.I, w.C), float("nan"), dtype=torch.bfloat16, device="cuda"),
+              torch.full((w.C, w.I), float("nan"), dtype=torch.bfloat16, device="cuda")]
+        run_layer(p, w, bufs, hidden, grad, dw)
+        results.append([hidden, grad] + dw)
+    for other in results[1:]:
+        for a, b in zip(results[0], other):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16))
