@@ -97,8 +97,9 @@ int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx,
  * where R_max = R if R >= 0 else T.  The size queries never decrease as R_max grows, so
  * buffers sized once for a bound serve every call with fewer rows.
  * R == 0 or T == 0: no arithmetic (out-of-place: plain copy).
- * Results are deterministic: every reduction has a fixed order, for every row count (the
- * GEMMs pick their tile height and K split from R_max, C and I alone). */
+ * Results are deterministic: every reduction has a fixed order.  The GEMMs pick their tile
+ * height and K split from the row bound of the call (R, or T when R = -1), C and I, so the
+ * same data may round differently in the last bit under a different bound. */
 size_t skipffn_saved_bytes(int64_t R_max, int64_t C, int64_t I);
 size_t skipffn_forward_workspace_bytes(int64_t R_max, int64_t C, int64_t I, int has_saved);
 int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps,
