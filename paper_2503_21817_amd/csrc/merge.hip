@@ -8,7 +8,9 @@
 // the sets' row offsets travel in the kernel arguments, so nothing is copied to the device).
 // Decisions that depend on floating point (which tokens are kept, where a token goes) are
 // taken on the float32 averages / similarities computed here, with ties to the lower index,
-// so they are unique for those values.
+// so they are unique for those values.  A token with a non-finite feature has NaN similarities:
+// its average ranks after every number, so exactly min(k, n) tokens are kept whatever the input;
+// a token whose similarities are all NaN goes to no slot (assign = -1) and gets a zero gradient.
 #include "kernels.hpp"
 #include "segments.hpp"
 
@@ -97,7 +99,7 @@ __global__ __launch_bounds__(MG_THREADS) void merge_slot_kernel(const uint8_t* _
     for (int u = 0; u < tid; ++u) slot += cnt[u];
     int32_t* kout = kept_idx + (int64_t)(set_base + set) * k;
     for (int t = b; t < e; ++t) {
-        if (kept[lo + t]) {
+        if (kept[lo + t] && slot < k) {      // the rank order is total, so slot < k always holds: belt and braces
             slot_of[lo + t] = slot;
             kout[slot] = lo + t;
             ++slot;

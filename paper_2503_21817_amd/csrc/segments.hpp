@@ -59,17 +59,23 @@ __device__ __forceinline__ void unpack8s(const u32x4& v, float* f) {
     }
 }
 
-// Number of entries u of vals[0..n) (an LDS array) that come before entry t in the order
-// "DESCENDING ? larger first : smaller first", equal values ordered by index.  (One value per
-// LDS read: a four-wide version was measured twice as slow.)
+// Whether entry (v, u) comes before entry (vt, t) in the order "DESCENDING ? larger first :
+// smaller first", equal values ordered by index.  The order is total: a NaN comes after every
+// number (NaNs among themselves by index), so exactly min(k, n) entries have rank < k whatever
+// the values are.
+template <bool DESCENDING>
+__device__ __forceinline__ bool ranks_before(float v, int u, float vt, int t) {
+    const bool vn = v != v, tn = vt != vt;
+    const bool first = DESCENDING ? v > vt : v < vt;           // false when either is NaN
+    const bool same = (v == vt) || (vn && tn);
+    return first || (!vn && tn) || (same && u < t);
+}
+// Number of entries u of vals[0..n) (an LDS array) that come before entry t in that order.
+// (One value per LDS read: a four-wide version was measured twice as slow.)
 template <bool DESCENDING>
 __device__ __forceinline__ int rank_in_lds(const float* vals, int n, int t, float vt) {
     int before = 0;
-    for (int u = 0; u < n; ++u) {
-        const float v = vals[u];
-        const bool first = DESCENDING ? v > vt : v < vt;
-        before += (first || (v == vt && u < t)) ? 1 : 0;
-    }
+    for (int u = 0; u < n; ++u) before += ranks_before<DESCENDING>(vals[u], u, vt, t) ? 1 : 0;
     return before;
 }
 

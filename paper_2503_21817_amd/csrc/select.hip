@@ -2,8 +2,8 @@
 // sequence, the n visual tokens whose features are most similar (cosine) to the CLS token
 // are retained (mask 0), the rest are skipped (mask 1).  Two kernels: similarities (memory-
 // bound, features read once), then a rank count per sequence (a token is retained iff fewer
-// than n tokens beat it; equal similarities: the lower index wins), which needs no sort and
-// gives the unique answer for the similarities computed.
+// than n tokens beat it; equal similarities: the lower index wins; a NaN similarity loses to
+// every number), which needs no sort and gives the unique answer for the similarities computed.
 #include "kernels.hpp"
 #include "segments.hpp"
 
@@ -100,8 +100,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topn_kernel(
         beats = rank_in_lds<true>(ssim, n, t, st);
     } else {
         for (int u = 0; u < n; ++u) {
-            const float su = sim[lo + u];
-            beats += (su > st || (su == st && u < t)) ? 1 : 0;
+            beats += ranks_before<true>(sim[lo + u], u, st, t) ? 1 : 0;
         }
     }
     const uint8_t m = beats < keep ? 0 : 1;

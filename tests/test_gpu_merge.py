@@ -159,3 +159,43 @@ def test_merge_gradient_passes_through_a_set_kept_whole_and_zeroes_invalid_slots
     assert np.all(got[6] == 0) and np.all(got[8] == 0)                          # -1 and an index >= min(k, n)
     ref = O.token_merge_backward(gb, [0, 5, 11], 8, np.where((assign < 0) | (assign > 5), -1, assign))
     assert np.array_equal(got, ref["dx_bits"])
+
+
+def test_non_finite_tokens_keep_exactly_k_and_stay_inside_the_outputs():
+    """One Inf / NaN row per set turns similarities and averages into NaN.  The rank order is
+    total (NaN after every number, then by index), so exactly min(k, n) tokens are kept per set and
+    nothing is written outside kept_idx / out: both are carved out of larger buffers whose
+    surrounding bytes must survive."""
+    rng = np.random.default_rng(31)
+    lens, C, k = (96, 130, 40), 256, 24
+    x = rng.standard_normal((sum(lens), C))
+    x[5, 17] = np.inf
+    x[96 + 129, :] = np.nan
+    x[96 + 130 + 1, 0] = -np.inf
+    xb = O.f64_to_bf16_bits(x)
+    seg = [0] + np.cumsum(lens).tolist()
+    S, n_tok = len(lens), sum(lens)
+    pad = 64
+    d_x = to_dev_bf16(xb)
+    out_big = torch.full((pad + S * k * C + pad,), 1.5, dtype=torch.bfloat16, device="cuda")
+    kept_big = torch.full((pad + S * k + pad,), -77, dtype=torch.int32, device="cuda")
+    assign_big = torch.full((pad + n_tok + pad,), -77, dtype=torch.int32, device="cuda")
+    avg_big = torch.full((pad + n_tok + pad,), 3.25, dtype=torch.float32, device="cuda")
+    out = out_big[pad:pad + S * k * C].view(S, k, C)
+    kept = kept_big[pad:pad + S * k].view(S, k)
+    assign = assign_big[pad:pad + n_tok]
+    avg = avg_big[pad:pad + n_tok]
+    ws = torch.empty(B.skipffn_token_merge_workspace_bytes(n_tok, max(lens), C), dtype=torch.uint8, device="cuda")
+    B.skipffn_token_merge(d_x, seg, k, out, kept, assign, avg, workspace=ws)
+    torch.cuda.synchronize()
+    for big, fill in ((out_big, 1.5), (kept_big, -77), (assign_big, -77), (avg_big, 3.25)):
+        assert bool((big[:pad] == fill).all()) and bool((big[-pad:] == fill).all())
+    kept_h, assign_h, avg_h = kept.cpu().numpy(), assign.cpu().numpy(), avg.cpu().numpy()
+    for s in range(S):
+        lo, hi = seg[s], seg[s + 1]
+        kk = min(k, hi - lo)
+        # the oracle's rule (a stable sort, NaN last) on the GPU's own averages
+        want = np.sort(np.argsort(avg_h[lo:hi], kind="stable")[:kk]) + lo
+        assert np.array_equal(kept_h[s, :kk], want)
+        assert np.all((assign_h[lo:hi] >= -1) & (assign_h[lo:hi] < kk))
+        assert np.array_equal(assign_h[kept_h[s, :kk]], np.arange(kk))

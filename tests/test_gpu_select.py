@@ -91,3 +91,23 @@ def test_mask_scattered_to_token_positions_feeds_the_compaction():
     good = np.ones(n, bool); good[[3, 50]] = False
     want[pos[good]] = mask[good]
     assert np.array_equal(sk, want)
+
+
+def test_non_finite_features_still_retain_exactly_n():
+    """A feature row holding Inf or NaN has a NaN similarity.  NaN loses to every number (the
+    oracle's sort puts it last as well), so exactly n tokens are retained whatever the input."""
+    rng = np.random.default_rng(15)
+    f = rng.standard_normal((300, 128))
+    f[7, 3] = np.inf
+    f[100, :] = np.nan
+    f[299, 0] = -np.inf
+    feat = O.f64_to_bf16_bits(f)
+    cls = O.f64_to_bf16_bits(rng.standard_normal((2, 128)))
+    off = np.array([0, 120, 300], dtype=np.int32)
+    for keep in (1, 50, 119, 120, 179, 180):
+        mask, sim, _ = run_gpu(feat, cls, off, keep)
+        assert np.isnan(sim[[7, 100, 299]]).all() and np.isfinite(np.delete(sim, [7, 100, 299])).all()
+        for b in range(2):
+            lo, hi = off[b], off[b + 1]
+            assert int((mask[lo:hi] == 0).sum()) == min(keep, hi - lo)
+            assert np.array_equal(mask[lo:hi], O.select_top_n(sim[lo:hi], keep))
