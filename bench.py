@@ -10,7 +10,11 @@ kernel class with the largest share of the step (algorithmic FLOPs or bytes over
 HIP-event duration, against the published peak), `kernels` (every class the same way) and
 `cpu_baseline` (the fp64 numpy oracle timed on the host cores).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--passes fwd+bwd]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 5] [--passes fwd+bwd]
+
+The default workload is the largest single-GPU forward+backward configuration: 32 stacked
+layers at C=4096, I=14336 over 16 sequences of 576 visual + 40 text tokens, 25 % of the visual
+tokens retained (--config 1..4 select the others).
 """
 
 from __future__ import annotations
@@ -34,15 +38,41 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 MEASURED_MFMA_RANDOM_TFLOPS = 1900.0
 MEASURED_COPY_GBS = 5000.0
 
-# Bytes per launch that the L2s exchanged with the fabric / HBM for configuration 2, forward +
-# backward: rocprofv3 --pmc FETCH_SIZE (x 2.0, calibrated with a copy kernel) + WRITE_SIZE, from
-# profiles/bench_cfg2_fwd_bwd_hbm_traffic_and_mfma_counters.md.  Counters cannot be read from
-# inside this process, so the figure is the profiled one for the same launch configuration.
-MEASURED_TRAFFIC_CFG2_FWD_BWD = {
-    "gemm_gate_up_swiglu": 685.0e6, "gemm_down": 384.1e6, "gemm_dh_swiglu_bwd+dw_down": 998.3e6,
-    "gemm_dw_gate_up": 741.6e6, "gemm_dxn": 687.4e6, "gather_rmsnorm": 36.4e6,
-    "resid_scatter": 105.0e6, "rmsnorm_bwd_scatter": 117.2e6, "gather_rows": 30.2e6,
-}
+# Bytes per launch that the L2s exchanged with the fabric / HBM come from the tracked profile of
+# the same launch configuration: rocprofv3 --pmc FETCH_SIZE (x 2.0, calibrated with a copy kernel)
+# + WRITE_SIZE, summarised per kernel class in profiles/bench_cfg<N>_<passes>_hbm_traffic_and_mfma_counters.md.
+# Counters cannot be read from inside this process, so the figure is the profiled one.
+
+
+def profiled_traffic(cfg, passes):
+    """{kernel class: bytes per launch} from the tracked counter summary of this workload, or
+    {} when there is none.  Table rows read  | kernel | class | fetched MB | written MB | ..."""
+    name = f"bench_cfg{cfg}_{passes.replace('+', '_')}_hbm_traffic_and_mfma_counters.md"
+    path = os.path.join(ROOT, "profiles", name)
+    out = {}
+    if not os.path.exists(path):
+        return out
+    with open(path) as f:
+        for line in f:
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) < 4 or not line.lstrip().startswith("|"):
+                continue
+            try:
+                out[cells[1]] = (float(cells[2]) + float(cells[3])) * 1e6
+            except ValueError:
+                continue
+    return out
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def parse():
@@ -50,9 +80,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2,
-                    help="workload 1..5 (token mix and layer shape; 5 = 32 layers, forward 1..32 then "
-                         "backward 32..1)")
+    ap.add_argument("--config", type=int, default=5,
+                    help="workload 1..5 (token mix and layer shape); the default, 5, is the largest "
+                         "forward+backward configuration: 32 layers, forward 1..32 then backward 32..1")
     ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy", "mfma", "prefill"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
                          "tokens at the configuration's fixed T; compact: the mask compaction alone at "
@@ -130,10 +160,15 @@ def cpu_baseline(w, passes, target_s):
             dt += run(nseq)[0]
         reps += extra
     flops = reps * skipffn_flops(R, w.C, w.I, passes == "fwd+bwd")
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {nseq} of {len(lens)} sequences ({n} tokens, {R} retained), "
-                      f"{'one layer, ' if w.layers > 1 else ''}{passes}, fp64 numpy, {reps} pass(es), {dt:.1f} s",
-            "seconds": dt, "retained_tokens_per_s": reps * R / dt}
+    rec = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+           "cpu_model": cpu_model(),
+           "sample": f"first {nseq} of {len(lens)} sequences ({n} tokens, {R} retained), "
+                     f"{'one layer of ' + str(w.layers) + ', ' if w.layers > 1 else ''}{passes}, fp64 numpy, {reps} pass(es), {dt:.1f} s",
+           "seconds": dt, "retained_tokens_per_s": reps * R / dt}
+    # the whole step at that rate (all sequences, all layers): extrapolated, not run
+    full = w.layers * skipffn_flops(w.R, w.C, w.I, passes == "fwd+bwd")
+    rec["extrapolated_step_seconds"] = full / (flops / dt)
+    return rec
 
 
 def _time_steps(torch, fn, warmup, steps):
@@ -668,7 +703,7 @@ def main():
         achieved, peak, unit = amount / dom_avg_s / 1e9, PEAK_HBM_GBS, "GB/s"
     roofline = {"kernel": dom, "bound": kind, "achieved": round(achieved, 2), "peak": peak,
                 "unit": unit, "frac": round(achieved / peak, 4),
-                "traffic": (MEASURED_TRAFFIC_CFG2_FWD_BWD.get(dom) if (args.config == 2 and bwd) else None),
+                "traffic": (None if oop or args.graph else profiled_traffic(args.config, args.passes).get(dom)),
                 "avg_launch_ms": kernels[dom]["avg_ms"],
                 "frac_of_measured_ceiling": round(achieved / (MEASURED_MFMA_RANDOM_TFLOPS if kind == "mfma"
                                                               else MEASURED_COPY_GBS), 4)}

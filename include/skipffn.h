@@ -2,7 +2,7 @@
  * skipffn.h - C ABI of the MI355X (gfx950) Skip-FFN block.
  *
  * The block is the feed-forward half of one decoder layer under Skip-Vision
- * (Section 4.2 of the paper, "Training speed-up: skip FFN"):
+ * (Section 4.2 of the paper):
  *
  *     retained token :  h_out = h_attn + FFN(h_attn)
  *     skipped  token :  h_out = h_attn
@@ -53,7 +53,8 @@ typedef enum skipffn_status {
     SKIPFFN_ESHAPE = 2,       /* C or I not a multiple of 8, or a tensor >= 2 GiB */
     SKIPFFN_EWORKSPACE = 3,   /* workspace (or saved buffer) too small */
     SKIPFFN_EHIP = 4,         /* a HIP call failed; see skipffn_last_hip_error */
-    SKIPFFN_EUNSUPPORTED = 5  /* unknown flag bit */
+    SKIPFFN_EUNSUPPORTED = 5, /* unknown flag bit */
+    SKIPFFN_EIDX = 6          /* SKIPFFN_FLAG_VALIDATE_IDX: idx is not strictly ascending inside [0, T) */
 } skipffn_status;
 
 /* flags (bitwise or) */
@@ -62,7 +63,12 @@ typedef enum skipffn_status {
 #define SKIPFFN_FLAG_NO_RESIDUAL    0x4u  /* forward: retained rows get bf16(FFN(x)), not bf16(x + FFN(x)) - a debugging view */
 #define SKIPFFN_FLAG_BALANCED_SPLIT  0x8u  /* use the balanced K split of the down / dXn GEMMs whenever it applies
                                              (by default a cost model picks between it, plain split-K and no split) */
-#define SKIPFFN_FLAG_ALL            0xFu
+#define SKIPFFN_FLAG_VALIDATE_IDX    0x10u /* forward / backward, debugging: check idx[0..R) on the device first (strictly
+                                             ascending, inside [0, T)) and return SKIPFFN_EIDX, with nothing else
+                                             enqueued, when it is not.  The ONE case in which a call waits for the
+                                             stream (it reads the verdict back), so not for use under graph capture.
+                                             Without the flag idx is trusted: a wrong entry is an out-of-bounds write. */
+#define SKIPFFN_FLAG_ALL            0x1Fu
 
 /* ---- step 1: mask -> ascending retained indices -------------------------
  * Section 4.1 decides which visual tokens are retained; the block consumes
@@ -79,6 +85,14 @@ size_t skipffn_compact_workspace_bytes(int64_t T);
 int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx,
                     int32_t* num_retained, int32_t* pos,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* The same check as SKIPFFN_FLAG_VALIDATE_IDX, asynchronous (Section 4.2's retained set must be
+ * a set of token positions: the block scatters through it).  Enqueues two small kernels that
+ * write status[0] = 0 if idx[0..R) is strictly ascending and inside [0, T), else 1, and
+ * status[1] = the first offending position (INT32_MAX if none).
+ *   status  i32 [2] device OUT;  idx, R, num_retained as in the conventions.  No host wait. */
+int skipffn_validate_idx(const int32_t* idx, int64_t R, const int32_t* num_retained, int64_t T,
+                         int32_t* status, void* stream);
 
 /* ---- steps 2-4: forward of the block (Section 4.2, both equations) --------
  *   hidden  bf16 [T, C]  input (h_attn)

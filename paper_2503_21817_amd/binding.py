@@ -22,14 +22,16 @@ FLAG_DW_FP32 = 0x1
 FLAG_DW_ACCUMULATE = 0x2
 FLAG_NO_RESIDUAL = 0x4
 FLAG_BALANCED_SPLIT = 0x8
+FLAG_VALIDATE_IDX = 0x10
 
-OK, EINVAL, ESHAPE, EWORKSPACE, EHIP, EUNSUPPORTED = range(6)
+OK, EINVAL, ESHAPE, EWORKSPACE, EHIP, EUNSUPPORTED, EIDX = range(7)
 
 # every symbol include/skipffn.h declares: (restype, argtypes)
 _SIGNATURES = {
     "skipffn_compact_workspace_bytes": (c_size_t, [c_int64]),
     "skipffn_compact": (c_int, [c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
                                 c_size_t, c_void_p]),
+    "skipffn_validate_idx": (c_int, [c_void_p, c_int64, c_void_p, c_int64, c_void_p, c_void_p]),
     "skipffn_saved_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
     "skipffn_forward_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64, c_int]),
     "skipffn_forward": (c_int, [c_int64, c_int64, c_int64, c_float, c_void_p, c_void_p,
@@ -133,6 +135,12 @@ def skipffn_compact(skip_mask, idx, num_retained, pos=None, workspace=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().skipffn_compact(_ptr(skip_mask), T, _ptr(idx), _ptr(num_retained), _ptr(pos),
                                  _ptr(workspace), ws_bytes, _stream()), "skipffn_compact")
+
+
+def skipffn_validate_idx(idx, R, T, status, *, num_retained=None):
+    """status i32 [2] on the device: {0 ok / 1 bad, first offending position}; asynchronous."""
+    Rv, nr = _rargs(R, num_retained)
+    _check(lib().skipffn_validate_idx(_ptr(idx), Rv, nr, T, _ptr(status), _stream()), "skipffn_validate_idx")
 
 
 def skipffn_saved_bytes(R_max, C, I) -> int:

@@ -142,7 +142,7 @@ SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
     return L;
 }
 
-struct FwdWs { size_t xn, rstd, h, partial, gu_partial, total; };
+struct FwdWs { size_t xn, rstd, h, partial, gu_partial, status, total; };
 FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     FwdWs w; size_t o = 0;
     w.xn = o;   if (!has_saved) o += align_up((size_t)R * C * 2);
@@ -153,11 +153,12 @@ FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
     const size_t slab_rows = std::max<size_t>((size_t)kMaxSplits * R, (size_t)kMaxSplitsNarrow * std::min<int64_t>(R, 256));
     w.partial = o; o += align_up(slab_rows * C * 4);
     w.gu_partial = o; o += align_up(gate_up_partial_bytes(R, C, I));
+    w.status = o; o += 256;              // verdict of SKIPFFN_FLAG_VALIDATE_IDX
     w.total = o;
     return w;
 }
 
-struct BwdWs { size_t dy, dyT, dg, du, partial, gainp, total; };
+struct BwdWs { size_t dy, dyT, dg, du, partial, gainp, status, total; };
 BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
     BwdWs w; size_t o = 0;
     w.dy = o; o += align_up((size_t)R * C * 2);
@@ -166,6 +167,7 @@ BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
     w.du = o; o += align_up((size_t)R * I * 2);
     w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
     w.gainp = o; o += align_up(gain_partial_bytes(R, C));
+    w.status = o; o += 256;              // verdict of SKIPFFN_FLAG_VALIDATE_IDX
     w.total = o;
     return w;
 }
@@ -181,6 +183,18 @@ int check_common(int64_t T, int64_t C, int64_t I, int64_t R, const int32_t* num_
         Rb * I * 2 >= kMaxTensorBytes || T > 0x7fffffff)
         return SKIPFFN_ESHAPE;
     return SKIPFFN_OK;
+}
+
+// SKIPFFN_FLAG_VALIDATE_IDX: run the check, wait for it and read the verdict back
+int validate_idx_now(const int32_t* idx, int64_t Rb, const int32_t* r_dev, int64_t T, void* status_dev,
+                     hipStream_t s) {
+    int32_t* st = static_cast<int32_t*>(status_dev);
+    hipError_t e = launch_validate_idx(idx, (int)Rb, r_dev, T, st, s);
+    if (e != hipSuccess) return hip_fail(e);
+    int32_t host[2] = {0, 0};
+    if ((e = hipMemcpyAsync(host, st, sizeof(host), hipMemcpyDeviceToHost, s)) != hipSuccess) return hip_fail(e);
+    if ((e = hipStreamSynchronize(s)) != hipSuccess) return hip_fail(e);
+    return host[0] == 0 ? SKIPFFN_OK : SKIPFFN_EIDX;
 }
 
 bool partial_overlap(const void* a, const void* b, size_t bytes) {
@@ -235,6 +249,7 @@ const char* skipffn_status_string(int status) {
         case SKIPFFN_EWORKSPACE: return "workspace too small";
         case SKIPFFN_EHIP: return "HIP runtime error";
         case SKIPFFN_EUNSUPPORTED: return "unsupported flag";
+        case SKIPFFN_EIDX: return "idx is not strictly ascending inside [0, T)";
         default: return "unknown status";
     }
 }
@@ -332,6 +347,10 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         if (workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
     }
     if (T == 0) return SKIPFFN_OK;
+    if ((flags & SKIPFFN_FLAG_VALIDATE_IDX) && Rb > 0) {
+        st = validate_idx_now(idx, Rb, r_dev, T, static_cast<char*>(workspace) + fwd_ws(Rb, C, I, saved != nullptr).status, s);
+        if (st != SKIPFFN_OK) return st;
+    }
 
     hipError_t e;
     if (out != hidden) {
@@ -467,6 +486,10 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         if (workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
     }
 
+    if ((flags & SKIPFFN_FLAG_VALIDATE_IDX) && Rb > 0 && T > 0) {
+        st = validate_idx_now(idx, Rb, r_dev, T, static_cast<char*>(workspace) + bwd_ws(Rb, C, I).status, s);
+        if (st != SKIPFFN_OK) return st;
+    }
     hipError_t e;
     if (T > 0 && grad_hidden != grad_out) {
         e = launch_passthrough(grad_out, grad_hidden, T, C * 2, idx, (int)Rb, r_dev, s);
@@ -573,6 +596,17 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
                                    static_cast<float*>(d_rms_gain), accum ? 1 : 0, s);
     if (e != hipSuccess) return hip_fail(e);
     return SKIPFFN_OK;
+}
+
+int skipffn_validate_idx(const int32_t* idx, int64_t R, const int32_t* num_retained, int64_t T,
+                         int32_t* status, void* stream) {
+    if (T < 0 || T > 0x7fffffff || R < -1 || R > T) return SKIPFFN_EINVAL;
+    if (R == -1 && num_retained == nullptr) return SKIPFFN_EINVAL;
+    if (status == nullptr || (reinterpret_cast<uintptr_t>(status) & 3u)) return SKIPFFN_EINVAL;
+    const int64_t Rb = R < 0 ? T : R;
+    if (Rb > 0 && (idx == nullptr || (reinterpret_cast<uintptr_t>(idx) & 3u))) return SKIPFFN_EINVAL;
+    hipError_t e = launch_validate_idx(idx, (int)Rb, R < 0 ? num_retained : nullptr, T, status, (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 
 // ---- skip KV-cache row gather -------------------------------------------------------------------

@@ -178,4 +178,36 @@ hipError_t launch_compact(const uint8_t* mask, int64_t T, int32_t* idx, int32_t*
     return hipGetLastError();
 }
 
+// ---- index-list check (debugging aid of the forward / backward calls) ---------------------------
+// status[0] = 0 when idx[0..R) is strictly ascending and inside [0, T), else 1; status[1] = the
+// first offending position (INT_MAX when there is none).  Two launches: the first resets the
+// two words (a kernel, so that the sequence can be captured in a HIP graph).
+__global__ void idx_status_reset_kernel(int32_t* __restrict__ status) {
+    if (threadIdx.x == 0) { status[0] = 0; status[1] = 0x7fffffff; }
+}
+__global__ __launch_bounds__(256) void validate_idx_kernel(const int32_t* __restrict__ idx, int Rbound,
+                                                           const int32_t* __restrict__ r_dev, int64_t T,
+                                                           int32_t* __restrict__ status) {
+    const int R = effective_rows(Rbound, r_dev);
+    for (int r = blockIdx.x * 256 + threadIdx.x; r < R; r += gridDim.x * 256) {
+        const int v = idx[r];
+        const bool bad = v < 0 || (int64_t)v >= T || (r > 0 && idx[r - 1] >= v);
+        if (bad) {
+            atomicMin(&status[1], r);
+            status[0] = 1;
+        }
+    }
+}
+
+hipError_t launch_validate_idx(const int32_t* idx, int R, const int32_t* r_dev, int64_t T, int32_t* status,
+                               hipStream_t s) {
+    hipLaunchKernelGGL(idx_status_reset_kernel, dim3(1), dim3(64), 0, s, status);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || R <= 0) return e;
+    int blocks = (R + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(validate_idx_kernel, dim3(blocks), dim3(256), 0, s, idx, R, r_dev, T, status);
+    return hipGetLastError();
+}
+
 }  // namespace skipffn

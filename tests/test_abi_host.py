@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     lib = B.lib()
-    seen = {lib.skipffn_status_string(i).decode() for i in range(6)}
-    assert len(seen) == 6
+    seen = {lib.skipffn_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7
     assert "unknown" in lib.skipffn_status_string(99).decode()
 
 
@@ -90,6 +90,21 @@ def test_forward_rejects_bad_arguments_on_the_host():
     # T == 0 and R == 0 in place are valid no-ops that enqueue nothing
     assert fwd(T=0, R=0, hidden=None, out=None, idx=None, ws=None, ws_bytes=0) == B.OK
     assert fwd(R=0, idx=None, ws=None, ws_bytes=0) == B.OK
+    # the index check is a known flag bit; with nothing retained (or no tokens) nothing is enqueued
+    assert fwd(R=0, idx=None, ws=None, ws_bytes=0, flags=B.FLAG_VALIDATE_IDX) == B.OK
+    assert fwd(T=0, R=0, hidden=None, out=None, idx=None, ws=None, ws_bytes=0, flags=B.FLAG_VALIDATE_IDX) == B.OK
+    assert fwd(flags=0x20) == B.EUNSUPPORTED
+
+
+def test_validate_idx_rejects_bad_arguments_on_the_host():
+    v = B.lib().skipffn_validate_idx          # idx, R, num_retained, T, status, stream
+    assert v(FAKE, 4, None, -1, FAKE, None) == B.EINVAL
+    assert v(FAKE, 9, None, 8, FAKE, None) == B.EINVAL          # R > T
+    assert v(FAKE, -1, None, 8, FAKE, None) == B.EINVAL         # device count requested, no pointer
+    assert v(FAKE, 4, None, 8, None, None) == B.EINVAL          # no status words
+    assert v(FAKE, 4, None, 8, ODD, None) == B.EINVAL
+    assert v(None, 4, None, 8, FAKE, None) == B.EINVAL
+    assert v(ODD, 4, None, 8, FAKE, None) == B.EINVAL
 
 
 def test_backward_rejects_bad_arguments_on_the_host():
@@ -101,7 +116,9 @@ def test_backward_rejects_bad_arguments_on_the_host():
     assert bwd(saved=None) == B.EINVAL
     assert bwd(dwg=None) == B.EINVAL
     assert bwd(dwd=ODD) == B.EINVAL
-    assert bwd(flags=0x10) == B.EUNSUPPORTED
+    assert bwd(flags=0x20) == B.EUNSUPPORTED
+    # the index check is a known flag: with nothing retained it has nothing to look at
+    assert bwd(flags=B.FLAG_VALIDATE_IDX, ws_bytes=0) == B.EWORKSPACE
     assert bwd(ws_bytes=0) == B.EWORKSPACE
     assert bwd(dgain=ODD) == B.EINVAL
 
