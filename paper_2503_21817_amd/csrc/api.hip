@@ -3,11 +3,13 @@
 // carving and the launch sequences.  Declarations and the contract of every entry point are
 // in include/skipffn.h.
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
 #include "../../include/skipffn.h"
 #include "kernels.hpp"
+#include "layout.hpp"
 
 using namespace skipffn;
 
@@ -20,7 +22,6 @@ int hip_fail(hipError_t e) {
     return SKIPFFN_EHIP;
 }
 
-inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool bad_ptr(const void* p) { return p == nullptr || !aligned16(p); }
 constexpr int64_t kMaxTensorBytes = (int64_t)1 << 31;
@@ -39,137 +40,22 @@ hipError_t ensure_gemm_init() {
     return g_gemm_init_err;
 }
 
-constexpr int kMaxSplits = 8;
-constexpr int kMaxSplitsNarrow = 16;     // few rows: small fp32 slabs, and every CU has to stream weights
-
-// How the K range of a GEMM with tiles_m x tiles_n output tiles and `ktiles` K slabs is cut
-// on 256 CUs (one workgroup per CU).  Costs are in units of one K slab of one tile: every
-// round of 256 workgroups costs its slab count plus a fixed prologue/epilogue, partial tiles
-// cost a write now and a read in the reducing kernel.
-//   splits == 1, sk_nbg == 0 : one workgroup per tile, epilogue fused
-//   splits  > 1, sk_nbg == 0 : plain split-K into `splits` fp32 slabs
-//   sk_nbg  > 0              : balanced split (gemm_bf16_streamk_kernel), sk_nbg workgroups per
-//                              n-tile group (with more m-tiles than workgroups in a group, a
-//                              workgroup walks several tiles and only boundary tiles are shared)
-struct KPartition { int splits; int sk_nbg; };
-KPartition choose_k_partition(int tiles_m, int tiles_n, int ktiles, bool force_balanced) {
-    const int tiles = tiles_m * tiles_n;
-    KPartition best{1, 0};
-    double best_cost = 1e30;
-    for (int s = 1; s <= kMaxSplits; ++s) {
-        int per = (ktiles + s - 1) / s;
-        if (s > 1 && per < 8) break;
-        int rounds = (tiles * s + 255) / 256;
-        double cost = rounds * (per + 8.0 + (s > 1 ? 8.0 : 0.0)) + (s > 1 ? 0.04 * s * tiles : 0.0);
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{s, 0}; }
+// Compute units of the current device (one workgroup of the GEMM core occupies one CU), read once
+// per device; 256 - an MI355X - when no device can be queried (size queries on a host without a GPU).
+constexpr int kDefaultCus = 256;
+int num_cus() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) { (void)hipGetLastError(); return kDefaultCus; }
+    int v = cached[dev].load(std::memory_order_relaxed);
+    if (v > 0) return v;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return kDefaultCus;
     }
-    const int nbg = tiles_n > 0 ? 256 / tiles_n : 0;
-    if (nbg >= 1 && tiles > 0) {
-        const StreamKPlan p = streamk_plan(tiles_m, ktiles, nbg);
-        if (force_balanced) return KPartition{1, nbg};
-        if (p.q >= 8) {
-            double slabs = 0.0;
-            for (int i = 0; i < tiles_m; ++i) slabs += streamk_count(p, i);
-            // an aligned chunk is one segment; a remainder piece runs one segment (with its own
-            // prologue and epilogue: about 5 slabs' worth, measured) per tile it touches
-            const double aligned = p.a > 0 ? p.q + 16.0 : 0.0;
-            const double pieces = p.nr > 0 ? p.qr + 16.0 + 5.0 * (p.qr / p.rem) : 0.0;
-            double cost = std::max(aligned, pieces) + 0.04 * slabs * tiles_n;
-            if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{1, nbg}; }
-        }
-    }
-    return best;
-}
-
-// Few rows: the GEMMs of the forward pass run on 128-row tiles (twice the workgroups per row of
-// tiles, a loop bound by streaming the weights instead of by MFMA work on empty rows).
-// Measured at C=4096, I=14336: gate/up 86 -> 75 us and down 44 -> 38 us up to 128 rows, a few
-// per cent up to 256 rows, slower beyond (the half-height tiles are bound by the load / barrier
-// skeleton of the loop, not by MFMA work).
-inline bool narrow_rows(int64_t rows) { return rows <= 256; }
-// plain split-K for the 128-row tiles: fill the CUs, keep at least 8 slabs per workgroup
-KPartition choose_k_split_narrow(int tiles_m, int tiles_n, int ktiles) {
-    const int tiles = tiles_m * tiles_n;
-    KPartition best{1, 0};
-    double best_cost = 1e30;
-    for (int s = 1; s <= kMaxSplitsNarrow; ++s) {
-        const int per = (ktiles + s - 1) / s;
-        if (s > 1 && per < 8) break;
-        const int rounds = (tiles * s + 255) / 256;
-        const double cost = rounds * (per + 8.0 + (s > 1 ? 8.0 : 0.0)) + (s > 1 ? 0.02 * s * tiles : 0.0);
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{s, 0}; }
-    }
-    return best;
-}
-
-// Gate/up GEMM with few rows: one row of tiles has only I / 128 workgroups (112 for I = 14336), and a
-// workgroup cannot keep enough weight bytes in flight to make up for the idle CUs.  Up to 128 rows
-// the K range is therefore split over 2..4 workgroups per tile, which write fp32 partial sums of
-// gate and up; the SwiGLU moves to the reducing kernel.  0 = not used (fused epilogue instead).
-// Measured at C=4096, I=14336 (GEMM + reduction against the fused 128-row GEMM): 53 / 72 us at 16
-// rows, 57 / 71 at 64, 65 / 73 at 128; at 184 and 256 rows the partial sums (229 KB per row, written
-// and read) cost what the split gains.
-constexpr int64_t kGateUpSplitMaxRows = BM / 2;
-inline int gate_up_splits(int64_t rows, int64_t C, int64_t I) {
-    if (rows > kGateUpSplitMaxRows) return 0;
-    const int64_t tiles_n = (I + BN / 2 - 1) / (BN / 2), ktiles = (C + BK - 1) / BK;
-    int64_t s = std::min<int64_t>(4, 256 / std::max<int64_t>(tiles_n, 1));
-    while (s > 1 && ktiles / s < 8) --s;
-    return s >= 2 ? (int)s : 0;
-}
-inline size_t gate_up_partial_bytes(int64_t R, int64_t C, int64_t I) {
-    // sized for the largest row count that takes this path, so that a bound covers every smaller count
-    const int64_t rows = std::min<int64_t>(R, kGateUpSplitMaxRows);
-    const int s = gate_up_splits(rows, C, I);
-    const int64_t tiles_n = (I + BN / 2 - 1) / (BN / 2);
-    return s ? (size_t)s * (size_t)rows * (size_t)tiles_n * BN * 4 : 0;
-}
-
-inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
-
-struct SavedLayout { size_t off[7]; size_t total; };
-SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
-    SavedLayout L;
-    size_t o = 0;
-    L.off[0] = o; o += align_up((size_t)R * C * 2);
-    L.off[1] = o; o += align_up((size_t)R * C * 2);
-    L.off[2] = o; o += align_up((size_t)R * 4);
-    L.off[3] = o; o += align_up((size_t)R * I * 2);
-    L.off[4] = o; o += align_up((size_t)R * I * 2);
-    L.off[5] = o; o += align_up((size_t)R * I * 2);
-    L.off[6] = o; o += align_up((size_t)C * ld_transposed(R) * 2);
-    L.total = o;
-    return L;
-}
-
-struct FwdWs { size_t xn, rstd, h, partial, gu_partial, status, total; };
-FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved) {
-    FwdWs w; size_t o = 0;
-    w.xn = o;   if (!has_saved) o += align_up((size_t)R * C * 2);
-    w.rstd = o; if (!has_saved) o += align_up((size_t)R * 4);
-    w.h = o;    if (!has_saved) o += align_up((size_t)R * I * 2);
-    // a buffer sized for R_max rows must do for every smaller count: the 128-row variant (up to
-    // 256 rows) may use more slabs than the 256-row tiles
-    const size_t slab_rows = std::max<size_t>((size_t)kMaxSplits * R, (size_t)kMaxSplitsNarrow * std::min<int64_t>(R, 256));
-    w.partial = o; o += align_up(slab_rows * C * 4);
-    w.gu_partial = o; o += align_up(gate_up_partial_bytes(R, C, I));
-    w.status = o; o += 256;              // verdict of SKIPFFN_FLAG_VALIDATE_IDX
-    w.total = o;
-    return w;
-}
-
-struct BwdWs { size_t dy, dyT, dg, du, partial, gainp, status, total; };
-BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
-    BwdWs w; size_t o = 0;
-    w.dy = o; o += align_up((size_t)R * C * 2);
-    w.dyT = o; o += align_up((size_t)C * ld_transposed(R) * 2);
-    w.dg = o; o += align_up((size_t)R * I * 2);
-    w.du = o; o += align_up((size_t)R * I * 2);
-    w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
-    w.gainp = o; o += align_up(gain_partial_bytes(R, C));
-    w.status = o; o += 256;              // verdict of SKIPFFN_FLAG_VALIDATE_IDX
-    w.total = o;
-    return w;
+    cached[dev].store(n, std::memory_order_relaxed);
+    return n;
 }
 
 int check_common(int64_t T, int64_t C, int64_t I, int64_t R, const int32_t* num_retained,
@@ -315,7 +201,7 @@ int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets) {
 }
 size_t skipffn_forward_workspace_bytes(int64_t R_max, int64_t C, int64_t I, int has_saved) {
     if (R_max < 0 || C <= 0 || I <= 0) return 0;
-    return fwd_ws(R_max, C, I, has_saved != 0).total + 256;
+    return fwd_ws(R_max, C, I, has_saved != 0, num_cus()).total + 256;
 }
 size_t skipffn_backward_workspace_bytes(int64_t R_max, int64_t C, int64_t I) {
     if (R_max < 0 || C <= 0 || I <= 0) return 0;
@@ -342,13 +228,13 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
     if (Rb > 0) {
         if (idx == nullptr || (reinterpret_cast<uintptr_t>(idx) & 3u)) return SKIPFFN_EINVAL;
         if (bad_ptr(w_gate) || bad_ptr(w_up) || bad_ptr(w_down)) return SKIPFFN_EINVAL;
-        FwdWs W = fwd_ws(Rb, C, I, saved != nullptr);
+        FwdWs W = fwd_ws(Rb, C, I, saved != nullptr, num_cus());
         if (workspace == nullptr || !aligned16(workspace)) return SKIPFFN_EWORKSPACE;
         if (workspace_bytes < W.total) return SKIPFFN_EWORKSPACE;
     }
     if (T == 0) return SKIPFFN_OK;
     if ((flags & SKIPFFN_FLAG_VALIDATE_IDX) && Rb > 0) {
-        st = validate_idx_now(idx, Rb, r_dev, T, static_cast<char*>(workspace) + fwd_ws(Rb, C, I, saved != nullptr).status, s);
+        st = validate_idx_now(idx, Rb, r_dev, T, static_cast<char*>(workspace) + fwd_ws(Rb, C, I, saved != nullptr, num_cus()).status, s);
         if (st != SKIPFFN_OK) return st;
     }
 
@@ -360,7 +246,7 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
     if (Rb == 0) return SKIPFFN_OK;
     if ((e = ensure_gemm_init()) != hipSuccess) return hip_fail(e);
 
-    FwdWs W = fwd_ws(Rb, C, I, saved != nullptr);
+    FwdWs W = fwd_ws(Rb, C, I, saved != nullptr, num_cus());
     char* ws = static_cast<char*>(workspace);
     bf16_t *xrows = nullptr, *xn, *xnT = nullptr, *G = nullptr, *U = nullptr, *H;
     float* rstd;
@@ -400,7 +286,7 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         a.ldb = (int)C; a.b_bytes = (uint32_t)(I * C * 2);
         a.pairs = 1; a.splits = 1;
         a.out0 = H; a.out1 = G; a.out2 = U; a.ldo = (int)I;
-        const int gu_splits = gate_up_splits(Rb, C, I);
+        const int gu_splits = gate_up_splits(Rb, C, I, num_cus());
         profile_mark_begin(KC_GEMM_GATE_UP, s);
         if (gu_splits) {
             // few rows: split K on 128-row tiles, fp32 partial sums, SwiGLU in the reducing kernel
@@ -430,8 +316,8 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         const int tile_rows = a.narrow ? BM / 2 : BM;
         const int tiles_m = (int)((Rb + tile_rows - 1) / tile_rows), tiles_n = (int)((C + BN - 1) / BN);
         const int ktiles = (int)((I + BK - 1) / BK);
-        const KPartition kp = a.narrow ? choose_k_split_narrow(tiles_m, tiles_n, ktiles)
-                                       : choose_k_partition(tiles_m, tiles_n, ktiles, balanced);
+        const KPartition kp = a.narrow ? choose_k_split_narrow(tiles_m, tiles_n, ktiles, num_cus())
+                                       : choose_k_partition(tiles_m, tiles_n, ktiles, balanced, num_cus());
         a.splits = kp.splits;
         a.idx = idx; a.ldo = (int)C;
         a.no_residual = (flags & SKIPFFN_FLAG_NO_RESIDUAL) ? 1 : 0;
@@ -578,7 +464,8 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         a.pairs = 2;
         const int tiles_m = (int)((Rb + BM - 1) / BM), tiles_n = (int)((C + BN - 1) / BN);
         const int ktiles = 2 * (int)((I + BK - 1) / BK);
-        const KPartition kp = choose_k_partition(tiles_m, tiles_n, ktiles, (flags & SKIPFFN_FLAG_BALANCED_SPLIT) != 0);
+        const KPartition kp = choose_k_partition(tiles_m, tiles_n, ktiles, (flags & SKIPFFN_FLAG_BALANCED_SPLIT) != 0,
+                                                 num_cus());
         a.splits = kp.splits;
         pl = PartialLayout{kp.splits, kp.sk_nbg, ktiles};
         a.partial = partial;

@@ -29,11 +29,11 @@
 #pragma once
 
 #include "common.hpp"
+#include "layout.hpp"
 #include "streamk.hpp"
 
 namespace skipffn {
 
-constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int GEMM_THREADS = 512;
 constexpr int NSTAGE_A = 2, NSTAGE_B = 3;
 constexpr int OPER_BYTES = BM * BK * 2;             // 32 KB per operand slab

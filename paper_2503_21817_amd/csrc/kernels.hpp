@@ -82,8 +82,6 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl
                                       const float* rstd, const bf16_t* gain, const bf16_t* dY,
                                       const int32_t* idx, bf16_t* dX, float* gain_partial,
                                       float* dgain, int accumulate, hipStream_t s);
-// bytes of the gain-gradient scratch (one fp32 row of C per strip of rows)
-size_t gain_partial_bytes(int64_t R, int64_t C);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 
 // ---- adaptive summary layer -------------------------------------------------------------------

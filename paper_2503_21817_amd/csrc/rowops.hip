@@ -385,7 +385,6 @@ hipError_t launch_passthrough(const void* src, void* dst, int64_t T, int64_t row
 // With GAIN_GRAD a workgroup walks a strip of GAIN_STRIP rows and also accumulates the
 // gradient of the gain, dgain[c] = sum_r dxn[r][c] * x[r][c] * rstd[r], over its strip into
 // gpart[strip][c]; gain_grad_reduce_kernel adds the strips in order (deterministic).
-constexpr int GAIN_STRIP = 4;
 template <bool IN_REGS, bool GAIN_GRAD>
 __global__ __launch_bounds__(ROW_THREADS) void rmsnorm_bwd_scatter_kernel(
     const float* __restrict__ part, PartialLayout pl, int Rbound, const int32_t* __restrict__ r_dev,
@@ -584,10 +583,6 @@ hipError_t launch_rmsnorm_bwd_scatter(const float* dxn_partial, PartialLayout pl
     }
     profile_mark_end(KC_RMSNORM_BWD, s);
     return e;
-}
-
-size_t gain_partial_bytes(int64_t R, int64_t C) {
-    return (size_t)((R + GAIN_STRIP - 1) / GAIN_STRIP) * (size_t)C * 4;
 }
 
 // ---- zero fill (a kernel, so that it can be captured in a HIP graph) -----------------------
