@@ -33,6 +33,16 @@ def rel_l2(got: np.ndarray, want: np.ndarray) -> float:
     return float(num / den) if den > 0 else float(num)
 
 
+def max_slice_rel_l2(got: np.ndarray, want: np.ndarray, axis: int) -> float:
+    """Largest relative L2 error over the slices along `axis` (axis=1: per row, axis=0: per
+    column): one wrong tile edge, chunk or row cannot hide in the norm of a whole tensor."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    num = np.sqrt(np.einsum("ij,ij->i" if axis == 1 else "ij,ij->j", got - want, got - want))
+    den = np.sqrt(np.einsum("ij,ij->i" if axis == 1 else "ij,ij->j", want, want))
+    return float((num / np.maximum(den, 1e-300)).max())
+
+
 class Problem:
     """Host inputs of one workload plus their device copies."""
 

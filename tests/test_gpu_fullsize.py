@@ -11,7 +11,7 @@ import torch
 from oracle import skipffn_oracle as O
 from paper_2503_21817_amd import binding as B
 from paper_2503_21817_amd import workloads as W
-from helpers import REL_L2_TOL, Problem, bits_of, f64_of, rel_l2, to_dev_bf16
+from helpers import REL_L2_TOL, Problem, bits_of, f64_of, max_slice_rel_l2, rel_l2, to_dev_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -64,10 +64,86 @@ def test_full_size_forward_backward(cfg, structured):
     e = rel_l2(O.bf16_bits_to_f64(gh[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx]))
     print(f"  dx rel-L2 {e:.3e}", flush=True)
     assert e < REL_L2_TOL
+    # the same bound on every single row of dX, and on every row AND every column of the weight
+    # gradients: an error confined to one tile edge, one 16-byte chunk or one row cannot pass
+    er = max_slice_rel_l2(O.bf16_bits_to_f64(gh[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx]), axis=1)
+    print(f"  dx worst row {er:.3e}", flush=True)
+    assert er < REL_L2_TOL
     for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
-        e = rel_l2(f64_of(t), bo[k])
-        print(f"  {k} rel-L2 {e:.3e}", flush=True)
-        assert e < REL_L2_TOL, (k, e)
+        got = f64_of(t)
+        e = rel_l2(got, bo[k])
+        er, ec = max_slice_rel_l2(got, bo[k], axis=1), max_slice_rel_l2(got, bo[k], axis=0)
+        print(f"  {k} rel-L2 {e:.3e}, worst row {er:.3e}, worst column {ec:.3e}", flush=True)
+        assert e < REL_L2_TOL and er < REL_L2_TOL and ec < REL_L2_TOL, (k, e, er, ec)
+        del got
+
+    if cfg != 2:
+        return
+    # ---- the same step out of place, the weight gradients accumulated onto non-zero contents ----
+    # Retained rows must come out bit for bit as in place, skipped rows as copies; the
+    # accumulated gradients are compared with the oracle's sum, rounded once.
+    rng = np.random.default_rng(77)
+    prior = [O.f64_to_bf16_bits(rng.standard_normal(t.shape) * float(np.sqrt(np.mean(bo[k] ** 2))))
+             for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down"))]
+    acc = [to_dev_bf16(b) for b in prior]
+    out2 = torch.full_like(p.d_hidden, float("nan"))
+    g2 = torch.full_like(p.d_grad, float("nan"))
+    hid_in, grad_in = p.d_hidden.clone(), p.d_grad.clone()
+    B.skipffn_forward(hid_in, out2, bufs.idx, w.R, p.d_wg, p.d_wu, p.d_wd, eps=w.eps, saved=bufs.saved,
+                      workspace=bufs.fwd_ws)
+    B.skipffn_backward(grad_in, g2, bufs.idx, w.R, p.d_wg, p.d_wu, p.d_wd, bufs.saved, acc[0], acc[1], acc[2],
+                       eps=w.eps, workspace=bufs.bwd_ws, flags=B.FLAG_DW_ACCUMULATE)
+    torch.cuda.synchronize()
+    assert np.array_equal(bits_of(out2), out) and np.array_equal(bits_of(g2), gh)
+    assert np.array_equal(bits_of(hid_in), p.hidden) and np.array_equal(bits_of(grad_in), p.grad)   # inputs untouched
+    for t, b, k in zip(acc, prior, ("dw_gate", "dw_up", "dw_down")):
+        want = bo[k] + O.bf16_bits_to_f64(b)
+        got = f64_of(t)
+        e = rel_l2(got, want)
+        er, ec = max_slice_rel_l2(got, want, axis=1), max_slice_rel_l2(got, want, axis=0)
+        print(f"  accumulated {k} rel-L2 {e:.3e}, worst row {er:.3e}, worst column {ec:.3e}", flush=True)
+        assert e < REL_L2_TOL and er < REL_L2_TOL and ec < REL_L2_TOL, (k, e, er, ec)
+        # and the increment alone: what was added is the gradient (the sum is rounded once to bf16,
+        # 2^-9 of its size, on top of the gradient's own error)
+        inc = got - O.bf16_bits_to_f64(b)
+        assert rel_l2(inc, bo[k]) < REL_L2_TOL, k
+        del want, got, inc
+
+
+@pytest.mark.timeout(300)
+def test_a_non_finite_retained_row_stays_in_its_row():
+    """A retained token holding Inf (and one holding NaN) makes its own output and input-gradient
+    rows non-finite and nothing else: every other retained row still matches the oracle, skipped
+    rows are bit copies.  (The weight gradients sum over retained rows, so they are non-finite by
+    definition and are not looked at.)  Several row tiles, ragged tail, full layer width."""
+    w = W.small(C=4096, I=14336, visual=(700,), text=(33,), keep=(580,), seed=555, name="nonfinite-row")
+    print(f"non-finite row {w.name}: T={w.T} R={w.R}", flush=True)
+    p = Problem(w)
+    idx_h, R, _ = O.compact(p.mask)
+    r_inf, r_nan = int(idx_h[300]), int(idx_h[R - 1])            # mid tile, and the last retained row
+    p.hidden[r_inf, 17] = 0x7F80                                  # +Inf
+    p.hidden[r_nan, 4000] = 0x7FC0                                # NaN
+    p.d_hidden = to_dev_bf16(p.hidden)
+    bufs = B.SkipFFNBuffers(w.T, w.R, w.C, w.I)
+    hidden, grad = p.d_hidden.clone(), p.d_grad.clone()
+    dw = [torch.empty((w.I, w.C), dtype=torch.bfloat16, device="cuda"),
+          torch.empty((w.I, w.C), dtype=torch.bfloat16, device="cuda"),
+          torch.empty((w.C, w.I), dtype=torch.bfloat16, device="cuda")]
+    run_layer(p, w, bufs, hidden, grad, dw)
+    with np.errstate(all="ignore"):
+        fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, None, w.eps)
+        bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, None, w.eps)
+    out, gh, sk = bits_of(hidden), bits_of(grad), p.mask != 0
+    assert np.array_equal(out[sk], p.hidden[sk]) and np.array_equal(gh[sk], p.grad[sk])
+    good = np.array([t for t in idx_h if t not in (r_inf, r_nan)])
+    for name, got, want in (("out", out, fo["out_bits"]), ("dx", gh, bo["dx_bits"])):
+        g64, w64 = O.bf16_bits_to_f64(got), O.bf16_bits_to_f64(want)
+        assert np.isfinite(g64[good]).all(), name
+        assert not np.isfinite(g64[r_inf]).any() and not np.isfinite(g64[r_nan]).any(), name
+        assert not np.isfinite(w64[r_inf]).any() and not np.isfinite(w64[r_nan]).any(), name      # so says the definition
+        e, er = rel_l2(g64[good], w64[good]), max_slice_rel_l2(g64[good], w64[good], axis=1)
+        print(f"  {name} rel-L2 on the finite rows {e:.3e}, worst row {er:.3e}", flush=True)
+        assert e < REL_L2_TOL and er < REL_L2_TOL, name
 
 
 @pytest.mark.timeout(1500)
@@ -83,7 +159,7 @@ def test_cfg5_32_stacked_layers():
     saved = [torch.empty(B.skipffn_saved_bytes(w.R, w.C, w.I), dtype=torch.uint8, device="cuda")
              for _ in range(L)]
     bwd_ws = torch.empty(B.skipffn_backward_workspace_bytes(w.R, w.C, w.I), dtype=torch.uint8, device="cuda")
-    check_layers = [0, 13, L - 1]
+    check_layers = [0, 5, 13, 21, 27, L - 1]
     host_w = {}
     dev_w = []
     # trajectories of a few retained tokens through all layers on the CPU: per-token
