@@ -94,7 +94,8 @@ def test_mask_scattered_to_token_positions_feeds_the_compaction():
 
 
 def test_non_finite_features_still_retain_exactly_n():
-    """A feature row holding Inf or NaN has a NaN similarity.  NaN loses to every number (the
+    """A feature row holding Inf has a NaN similarity (Inf / Inf); a row that is NaN throughout has
+    no length at all and gets similarity 0, like a zero row.  NaN loses to every number (the
     oracle's sort puts it last as well), so exactly n tokens are retained whatever the input."""
     rng = np.random.default_rng(15)
     f = rng.standard_normal((300, 128))
@@ -106,7 +107,8 @@ def test_non_finite_features_still_retain_exactly_n():
     off = np.array([0, 120, 300], dtype=np.int32)
     for keep in (1, 50, 119, 120, 179, 180):
         mask, sim, _ = run_gpu(feat, cls, off, keep)
-        assert np.isnan(sim[[7, 100, 299]]).all() and np.isfinite(np.delete(sim, [7, 100, 299])).all()
+        assert np.isnan(sim[[7, 299]]).all() and sim[100] == 0.0
+        assert np.isfinite(np.delete(sim, [7, 299])).all()
         for b in range(2):
             lo, hi = off[b], off[b + 1]
             assert int((mask[lo:hi] == 0).sum()) == min(keep, hi - lo)

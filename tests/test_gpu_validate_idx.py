@@ -59,8 +59,8 @@ def test_flag_rejects_a_bad_list_before_anything_is_written():
         h = p.d_hidden.clone()
         out = torch.full_like(h, 3.0)
         with pytest.raises(B.SkipFFNError) as ei:
-            B.skipffn_forward(h, out, bad, w.R, p.d_wg, p.d_wu, p.d_wd, eps=w.eps, workspace=bufs.fwd_ws,
-                              flags=B.FLAG_VALIDATE_IDX)
+            B.skipffn_forward(h, out, bad, w.R, p.d_wg, p.d_wu, p.d_wd, eps=w.eps, saved=bufs.saved,
+                              workspace=bufs.fwd_ws, flags=B.FLAG_VALIDATE_IDX)
         assert ei.value.status == B.EIDX
         torch.cuda.synchronize()
         assert bool((out == 3.0).all()) and torch.equal(h.view(torch.int16), p.d_hidden.view(torch.int16))
