@@ -86,6 +86,19 @@ int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx,
                     int32_t* num_retained, int32_t* pos,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* skipffn_compact for callers that cannot allocate device memory and so have no workspace to
+ * hand over: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, outputs and guarantees as skipffn_compact minus the workspace: the
+ * few kilobytes of scratch the multi-block path needs (T above 262144) live in a 32 KB array
+ * inside the library, one copy per GPU, held until the process ends.  The call allocates and
+ * frees nothing.  T may be at most skipffn_compact_static_max_tokens() (2^28); a larger T returns
+ * SKIPFFN_ESHAPE with nothing enqueued.  Every call on a GPU uses that GPU's one array: calls
+ * that may overlap in time on the same GPU (different streams without ordering) race - give
+ * those skipffn_compact with a workspace each. */
+int64_t skipffn_compact_static_max_tokens(void);
+int skipffn_compact_static(const uint8_t* skip_mask, int64_t T, int32_t* idx,
+                           int32_t* num_retained, int32_t* pos, void* stream);
+
 /* The same check as SKIPFFN_FLAG_VALIDATE_IDX, asynchronous (Section 4.2's retained set must be
  * a set of token positions: the block scatters through it).  Enqueues two small kernels that
  * write status[0] = 0 if idx[0..R) is strictly ascending and inside [0, T), else 1, and

@@ -31,6 +31,8 @@ _SIGNATURES = {
     "skipffn_compact_workspace_bytes": (c_size_t, [c_int64]),
     "skipffn_compact": (c_int, [c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
                                 c_size_t, c_void_p]),
+    "skipffn_compact_static_max_tokens": (c_int64, []),
+    "skipffn_compact_static": (c_int, [c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_void_p]),
     "skipffn_validate_idx": (c_int, [c_void_p, c_int64, c_void_p, c_int64, c_void_p, c_void_p]),
     "skipffn_saved_bytes": (c_size_t, [c_int64, c_int64, c_int64]),
     "skipffn_forward_workspace_bytes": (c_size_t, [c_int64, c_int64, c_int64, c_int]),
@@ -135,6 +137,17 @@ def skipffn_compact(skip_mask, idx, num_retained, pos=None, workspace=None):
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().skipffn_compact(_ptr(skip_mask), T, _ptr(idx), _ptr(num_retained), _ptr(pos),
                                  _ptr(workspace), ws_bytes, _stream()), "skipffn_compact")
+
+
+def skipffn_compact_static_max_tokens() -> int:
+    return lib().skipffn_compact_static_max_tokens()
+
+
+def skipffn_compact_static(skip_mask, idx, num_retained, pos=None):
+    """skipffn_compact without a workspace: the library's own per-GPU scratch is used."""
+    T = skip_mask.numel()
+    _check(lib().skipffn_compact_static(_ptr(skip_mask), T, _ptr(idx), _ptr(num_retained), _ptr(pos), _stream()),
+           "skipffn_compact_static")
 
 
 def skipffn_validate_idx(idx, R, T, status, *, num_retained=None):

@@ -131,7 +131,7 @@ const char* skipffn_status_string(int status) {
     switch (status) {
         case SKIPFFN_OK: return "ok";
         case SKIPFFN_EINVAL: return "invalid argument (null or misaligned pointer, negative size, R > T)";
-        case SKIPFFN_ESHAPE: return "unsupported shape (C, I must be multiples of 8; tensors below 2 GiB)";
+        case SKIPFFN_ESHAPE: return "unsupported shape (C, I must be multiples of 8; tensors below 2 GiB; skipffn_compact_static: T above skipffn_compact_static_max_tokens())";
         case SKIPFFN_EWORKSPACE: return "workspace too small";
         case SKIPFFN_EHIP: return "HIP runtime error";
         case SKIPFFN_EUNSUPPORTED: return "unsupported flag";
@@ -185,6 +185,20 @@ int skipffn_compact(const uint8_t* skip_mask, int64_t T, int32_t* idx, int32_t* 
     size_t need = compact_workspace_bytes(T);
     if (workspace_bytes < need || (need > 0 && workspace == nullptr)) return SKIPFFN_EWORKSPACE;
     hipError_t e = launch_compact(skip_mask, T, idx, num_retained, pos, workspace, (hipStream_t)stream);
+    return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
+}
+
+int64_t skipffn_compact_static_max_tokens(void) { return compact_static_max_tokens(); }
+
+int skipffn_compact_static(const uint8_t* skip_mask, int64_t T, int32_t* idx, int32_t* num_retained,
+                           int32_t* pos, void* stream) {
+    if (T < 0 || T > 0x7fffffff || num_retained == nullptr) return SKIPFFN_EINVAL;
+    if (T > compact_static_max_tokens()) return SKIPFFN_ESHAPE;      // beyond the built-in scratch
+    if (T > 0 && (bad_ptr(skip_mask) || idx == nullptr)) return SKIPFFN_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(idx) & 3u) || (reinterpret_cast<uintptr_t>(pos) & 3u) ||
+        (reinterpret_cast<uintptr_t>(num_retained) & 3u))
+        return SKIPFFN_EINVAL;
+    hipError_t e = launch_compact_static(skip_mask, T, idx, num_retained, pos, (hipStream_t)stream);
     return e == hipSuccess ? SKIPFFN_OK : hip_fail(e);
 }
 

@@ -10,6 +10,8 @@
 // and deterministic.  Small inputs (every configuration of the block itself) use
 // one block and one launch; large masks use count / scan / write launches with
 // no spinning between blocks.
+#include <mutex>
+
 #include "kernels.hpp"
 
 namespace skipffn {
@@ -176,6 +178,44 @@ hipError_t launch_compact(const uint8_t* mask, int64_t T, int32_t* idx, int32_t*
                        num_retained, pos, (int32_t*)nullptr, offset);
     profile_mark_end(KC_COMPACT, s);
     return hipGetLastError();
+}
+
+// ---- compaction with the library's own scratch (callers that cannot allocate) ---------------------
+// The count / offset arrays of the multi-block path live in a file-scope device array instead of
+// a caller workspace.  Each GPU the library runs on holds its own copy of the array at its own
+// address; the address is looked up once per device, with that device current, and host code
+// uses that pointer only (the array's name is a host-side stand-in, not a device address).
+// Nothing in the array has to start at zero: every launch writes the counts and offsets of the
+// blocks it uses before reading them.  Calls that overlap in time on one GPU share the array
+// and race; calls on one stream (or otherwise ordered) do not.
+constexpr int CP_STATIC_MAX_BLOCKS = 4096;                       // 32 KB of scratch per GPU
+static __device__ __align__(256) int32_t scratch[2 * CP_STATIC_MAX_BLOCKS];
+
+int64_t compact_static_max_tokens() { return (int64_t)CP_STATIC_MAX_BLOCKS * CP_BLOCK_SPAN; }
+
+constexpr int CP_MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static int32_t* g_scratch_ptr[CP_MAX_DEVICES];
+
+hipError_t launch_compact_static(const uint8_t* mask, int64_t T, int32_t* idx, int32_t* num_retained,
+                                 int32_t* pos, hipStream_t s) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= CP_MAX_DEVICES) return hipErrorInvalidDevice;
+    int32_t* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        if (g_scratch_ptr[dev] == nullptr) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (p == nullptr) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev] = static_cast<int32_t*>(p);
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    return launch_compact(mask, T, idx, num_retained, pos, ptr, s);
 }
 
 // ---- index-list check (debugging aid of the forward / backward calls) ---------------------------

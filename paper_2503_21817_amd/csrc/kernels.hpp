@@ -40,6 +40,10 @@ size_t compact_workspace_bytes(int64_t T);
 hipError_t launch_compact(const uint8_t* mask, int64_t T, int32_t* idx, int32_t* num_retained,
                           int32_t* pos, void* ws, hipStream_t s);
 
+// the same with the library's own per-GPU scratch (no workspace, nothing allocated), T <= compact_static_max_tokens()
+int64_t compact_static_max_tokens();
+hipError_t launch_compact_static(const uint8_t* mask, int64_t T, int32_t* idx, int32_t* num_retained,
+                                 int32_t* pos, hipStream_t s);
 // status[0] = 0 if idx[0..R) is strictly ascending inside [0, T) else 1; status[1] = first bad position
 hipError_t launch_validate_idx(const int32_t* idx, int R, const int32_t* r_dev, int64_t T, int32_t* status,
                                hipStream_t s);
