@@ -72,6 +72,8 @@ struct GemmArgs {
     int accumulate;              // EPI_STORE: 1 = +=
     int no_residual;             // EPI_RESID_SCATTER: 1 = do not add the residual
     int narrow;                  // host side: 1 = launch the 128-row tile variant (tiles_m counts 128-row tiles)
+    int tail_narrow;             // 1 = the rows past tiles_m * 256 (at most 128 of them) form one extra row of
+                                 // 128-row tiles, run by the last tiles_n workgroups of the grid
 };
 
 // Row offsets of up to SEG_TABLE_MAX token sets, passed by value in the kernel arguments
@@ -665,10 +667,37 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     }
 }
 
+// The gate/up GEMM may end in a row of 128-row tiles: a row count just above a multiple of 256
+// then costs half a tile row instead of a whole one (R = 2944 = 11.5 tile rows: 1288 tile units
+// of work instead of 1344), and the half-height tiles, dispatched last, even out the end of the
+// grid (measured 635 -> 597 us).  The dH GEMM does not get it: its 128-row tiles are bound by the
+// memory phases of the N-contiguous weight operand and take as long as full ones, and the extra
+// code path cost the shared dH + dW_down kernel 2 % (713 -> 730 us with the path unused).
+template <bool A_KC, int EPI>
+constexpr bool kTailNarrowOk = A_KC && EPI == EPI_SWIGLU;
+
 // One workgroup's share of a plain (optionally split-K, optionally batched) GEMM: `block` of
 // `nblocks` in the launch order of this problem.
 template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const int nblocks) {
+    const int Meff = effective_rows(P.M, P.m_dev);
+    const int Keff = effective_rows(P.K, P.k_dev);
+    if constexpr (!NARROW && kTailNarrowOk<A_KC, EPI>) {
+        // host contract: tail_narrow comes with splits == 1, batch == 1 and a host-side row count
+        const int full = P.tiles_m * P.tiles_n;
+        if (P.tail_narrow && block >= full) {
+            const int ktotal = ((Keff + BK - 1) / BK) * P.pairs;
+            gemm_tile<A_KC, B_KC, EPI, true>(P, 2 * P.tiles_m, block - full, 0, 0, ktotal, Meff, Keff);
+            return;
+        }
+        if (P.tail_narrow) {
+            int tm, tn, z;
+            tile_of_block(block, full, P.tiles_m, P.tiles_n, tm, tn, z);
+            const int ktotal = ((Keff + BK - 1) / BK) * P.pairs;
+            gemm_tile<A_KC, B_KC, EPI, false>(P, tm, tn, 0, 0, ktotal, Meff, Keff);
+            return;
+        }
+    }
     int tm, tn, z;
     tile_of_block(block, nblocks, P.tiles_m, P.tiles_n, tm, tn, z);
     // batched launch (two problems in one grid, used for dW_gate / dW_up): the upper half of
@@ -679,8 +708,6 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
         if (EPI == EPI_STORE_T) P.B0 = P.B1; else P.A0 = P.A1;
         P.out0 = P.out1;
     }
-    const int Meff = effective_rows(P.M, P.m_dev);
-    const int Keff = effective_rows(P.K, P.k_dev);
     if (tm * (NARROW ? BM / 2 : BM) >= Meff) return;    // whole block leaves together: no barrier was reached yet
     const int ktotal = ((Keff + BK - 1) / BK) * P.pairs;
     const int per_split = (ktotal + P.splits - 1) / P.splits;

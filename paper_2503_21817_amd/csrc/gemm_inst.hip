@@ -39,27 +39,37 @@ hipError_t gemm_init() {
     return hipSuccess;
 }
 
-template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
-static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
-    const unsigned blocks = (unsigned)(a.tiles_m * a.tiles_n * a.splits * a.batch);
-    hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI, NARROW>), dim3(blocks), dim3(GEMM_THREADS),
-                       GEMM_LDS_BYTES, s, a);
-    return hipGetLastError();
-}
-
 static void finish_args(int epi, GemmArgs& a) {
     const int tm_rows = a.narrow ? BM / 2 : BM;
     a.tiles_m = (a.M + tm_rows - 1) / tm_rows;
     a.tiles_n = (epi == EPI_SWIGLU || epi == EPI_PARTIAL_GU) ? (a.N + BN / 2 - 1) / (BN / 2) : (a.N + BN - 1) / BN;
     if (a.splits < 1) a.splits = 1;
     if (a.batch < 1) a.batch = 1;
+    // a last tile row of at most 128 rows runs on 128-row tiles (host-side row count, one
+    // workgroup per tile: the gate/up GEMM)
+    const int rem = a.M % BM;
+    a.tail_narrow = (!a.narrow && epi == EPI_SWIGLU && a.m_dev == nullptr &&
+                     a.splits == 1 && a.batch == 1 && rem > 0 && rem <= BM / 2) ? 1 : 0;
+    if (a.tail_narrow) a.tiles_m = a.M / BM;           // full tile rows only; the tail row is extra
+}
+// workgroups of a one-tile-per-workgroup launch
+static unsigned grid_blocks(const GemmArgs& a) {
+    return (unsigned)(a.tiles_m * a.tiles_n * a.splits * a.batch + (a.tail_narrow ? a.tiles_n : 0));
+}
+
+template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
+    const unsigned blocks = grid_blocks(a);
+    hipLaunchKernelGGL((gemm_bf16_kernel<A_KC, B_KC, EPI, NARROW>), dim3(blocks), dim3(GEMM_THREADS),
+                       GEMM_LDS_BYTES, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s) {
     if (which != DUAL_DH_DWDOWN) return hipErrorInvalidValue;
     finish_args(EPI_SWIGLU_BWD, a0);
     finish_args(EPI_STORE, a1);
-    const int real0 = a0.tiles_m * a0.tiles_n * a0.splits * a0.batch;
+    const int real0 = (int)grid_blocks(a0);
     const int n0 = (real0 + 7) / 8 * 8;
     const int n1 = a1.tiles_m * a1.tiles_n * a1.splits * a1.batch;
     if (real0 <= 0 || n1 <= 0) return hipErrorInvalidValue;
@@ -101,7 +111,7 @@ hipError_t launch_gemm_selfsim(const bf16_t* xn, int C, const SegTable& st, int 
 
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s) {
     finish_args(epi, a);
-    if (a.tiles_m <= 0 || a.tiles_n <= 0) return hipSuccess;
+    if (grid_blocks(a) == 0 || a.tiles_n <= 0) return hipSuccess;
     if (a.narrow) {
         if (a_kc && b_kc && epi == EPI_SWIGLU) return launch_one<true, true, EPI_SWIGLU, true>(a, s);
         if (a_kc && b_kc && epi == EPI_PARTIAL) return launch_one<true, true, EPI_PARTIAL, true>(a, s);

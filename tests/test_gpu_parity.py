@@ -499,3 +499,32 @@ def test_buffers_sized_for_a_larger_row_bound(R_max):
     assert rel_l2(O.bf16_bits_to_f64(bits_of(gh)[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
     for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
         assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, k
+
+
+@pytest.mark.parametrize("R", [257, 300, 384, 385, 512 + 1, 512 + 128, 768 + 100])
+def test_last_tile_row_of_at_most_128_rows(R):
+    """A row count that leaves at most 128 rows for the last row of tiles runs that row on
+    128-row tiles in the gate/up GEMM (257, 300, 384, 513, 640, 868; 385 leaves 129 rows
+    and keeps a full-height tile).  Every row is checked on its own: the tail rows sit in
+    different tiles from the rest.  The intermediate width leaves a ragged column tile too."""
+    from helpers import max_slice_rel_l2
+    w = W.small(C=520, I=1368, visual=(R + 30,), text=(9,), keep=(R - 9,), seed=900 + R, name=f"tail-{R}")
+    assert w.R == R
+    print(f"tail row R={R} T={w.T}", flush=True)
+    p = Problem(w)
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, None, w.eps)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, None, w.eps)
+    idx, sk = fo["idx"], p.mask != 0
+    out, bufs = gpu_forward(p, saved=True, inplace=True)
+    got = bits_of(out)
+    assert np.array_equal(got[sk], p.hidden[sk])
+    assert max_slice_rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx]), axis=1) < REL_L2_TOL
+    sv = bufs.saved_views(R)
+    for k in ("G", "U", "H"):
+        assert max_slice_rel_l2(f64_of(sv[k]), fo[k], axis=1) < REL_L2_TOL, k
+    gh, dw = gpu_backward(p, bufs)
+    gb = bits_of(gh)
+    assert np.array_equal(gb[sk], p.grad[sk])
+    assert max_slice_rel_l2(O.bf16_bits_to_f64(gb[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx]), axis=1) < REL_L2_TOL
+    for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+        assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, k
