@@ -57,6 +57,13 @@ def profiled_traffic(cfg, passes):
             cells = [c.strip() for c in line.strip().strip("|").split("|")]
             if len(cells) < 4 or not line.lstrip().startswith("|"):
                 continue
+            if cells[1] in out:          # the traffic table comes first; later tables repeat the class column
+                continue
+            try:
+                float(cells[1])
+                continue                 # a table without the class column
+            except ValueError:
+                pass
             try:
                 out[cells[1]] = (float(cells[2]) + float(cells[3])) * 1e6
             except ValueError:
