@@ -90,14 +90,18 @@ def parse():
     ap.add_argument("--config", type=int, default=5,
                     help="workload 1..5 (token mix and layer shape); the default, 5, is the largest "
                          "forward+backward configuration: 32 layers, forward 1..32 then backward 32..1")
-    ap.add_argument("--sweep", default=None, choices=["retention", "compact", "kv", "summary", "select", "merge", "copy", "mfma", "prefill"],
+    ap.add_argument("--sweep", default=None, choices=["retention", "rows", "compact", "kv", "summary", "select", "merge", "copy", "mfma", "prefill"],
                     help="retention: time the step at retained fractions 0, 1/8, 1/4, 1/2, 1 of the visual "
-                         "tokens at the configuration's fixed T; compact: the mask compaction alone at "
+                         "tokens at the configuration's fixed T; rows: the step (one layer) at retained counts "
+                         "around multiples of the 256-row tile height, T = 16384; compact: the mask compaction alone at "
                          "T = 2^16 .. 2^26; kv: the skip KV-cache compaction of a whole LLaMA-3-8B cache "
                          "(32 layers x key/value x 8 heads x 128) for the token mixes of configurations "
                          "2, 3 and 5; summary: the adaptive summary layer, forward and backward, on "
                          "the visual token sets of the same mixes.  The JSON line then carries a 'sweep' array")
     ap.add_argument("--passes", default="fwd+bwd", choices=["fwd", "fwd+bwd"])
+    ap.add_argument("--structured", action="store_true",
+                    help="configuration 3 only: retain the leading 576 visual tokens of every sequence (the "
+                         "global view of a high-resolution image) instead of seeded-random positions")
     ap.add_argument("--out-of-place", action="store_true",
                     help="write to separate output / gradient tensors: skipped rows are then byte-copied "
                          "by the passthrough kernel (in place they cost nothing)")
@@ -241,6 +245,43 @@ def retention_sweep(torch, B, W, w, bwd, args):
                                    "in place"},
             "sweep": rows, "fit_ms": {"intercept": round(float(intercept), 4),
                                       "per_1000_retained": round(float(slope) * 1e3, 4)}}
+
+
+def rows_sweep(torch, B, bwd, args):
+    """One layer at C=4096, I=14336, T=16384 over retained counts just below, at and just above
+    multiples of the 256-row tile height (and the configurations' own counts): how much a nearly
+    empty last row of tiles costs."""
+    from paper_2503_21817_amd.flopmodel import skipffn_flops
+    C, I, T = 4096, 14336, 16384
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4200)
+    hid = torch.randn((T, C), generator=g, device="cuda").to(torch.bfloat16)
+    grad = torch.randn((T, C), generator=g, device="cuda").to(torch.bfloat16)
+    ws = [(torch.randn(shape, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+          for shape in ((I, C), (I, C), (C, I))]
+    dws = [torch.empty_like(w) for w in ws]
+    rows = []
+    for R in (1280, 1288, 1344, 1408, 1472, 1536, 2560, 2568, 2624, 2688, 2752, 2816, 2944, 3072, 3080, 4096, 4104,
+              4224, 8192, 8200, 9623):
+        mask = torch.ones(T, dtype=torch.uint8, device="cuda")
+        mask[torch.randperm(T, generator=g, device="cuda")[:R]] = 0
+        bufs = B.SkipFFNBuffers(T, R, C, I, training=bwd)
+        h, gg = hid.clone(), grad.clone()
+
+        def step(i):
+            B.skipffn_compact(mask, bufs.idx, bufs.num_retained, None, bufs.compact_ws)
+            B.skipffn_forward(h, h, bufs.idx, R, *ws, saved=bufs.saved, workspace=bufs.fwd_ws)
+            if bwd:
+                B.skipffn_backward(gg, gg, bufs.idx, R, *ws, bufs.saved, *dws, workspace=bufs.bwd_ws)
+
+        ms = _time_steps(torch, step, args.warmup, args.steps)
+        rows.append({"R": R, "tile_rows": round(R / 256, 3), "ms_per_step": round(ms, 4),
+                     "tflops": round(skipffn_flops(R, C, I, bwd) / (ms * 1e-3) / 1e12, 1),
+                     "us_per_retained_row": round(ms * 1e3 / R, 4)})
+        del bufs
+    return {"metric": "Skip-FFN step time against retained count around tile-row multiples", "unit": "ms",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"T={T} fixed, C={C}, I={I}, 1 layer, {args.passes}, in place"}, "sweep": rows}
 
 
 def prefill_sweep(torch, B, args):
@@ -561,8 +602,11 @@ def main():
         sys.exit(2)
     B.lib()   # fail loudly if the HIP library is missing
 
-    w = W.config(args.config)
+    w = W.config(args.config, structured=args.structured) if args.config == 3 else W.config(args.config)
     bwd = args.passes == "fwd+bwd"
+    if args.sweep == "rows":
+        print(json.dumps(rows_sweep(torch, B, bwd, args)))
+        return
     if args.sweep == "compact":
         print(json.dumps(compact_sweep(torch, B, args)))
         return
