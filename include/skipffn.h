@@ -118,7 +118,8 @@ int skipffn_validate_idx(const int32_t* idx, int64_t R, const int32_t* num_retai
  *   w_gate, w_up bf16 [I, C]; w_down bf16 [C, I]
  *   saved   NULL, or a buffer of skipffn_saved_bytes(R_max, C, I) bytes that
  *           receives what backward needs (gathered input rows, normalised
- *           rows and their transpose, 1/rms, gate, up and hidden activations); required for
+ *           rows, 1/rms, gate, up and hidden activations, and row-contiguous copies of the
+ *           normalised rows and of the hidden activations); required for
  *           training because an in-place forward overwrites its input.
  *   workspace: at least skipffn_forward_workspace_bytes(R_max, C, I, saved != NULL)
  * where R_max = R if R >= 0 else T.  The size queries never decrease as R_max grows, so
@@ -281,9 +282,11 @@ int skipffn_token_merge_backward(const void* grad_out, const int32_t* seg_host, 
  * Byte offsets of the sections inside a saved buffer for (R_max, C, I):
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];
  * [2] 1/rms f32 [R]; [3] gate bf16 [R, I]; [4] up bf16 [R, I];
- * [5] silu(gate)*up bf16 [R, I]; [6] normalised rows transposed, bf16 [C, ld] with
- * ld = R_max rounded up to a multiple of 8 (columns >= R are zero).
- * `offsets` is a HOST array of 7. */
+ * [5] silu(gate)*up bf16 [R, I]; [6] normalised rows transposed, bf16 [C, ld];
+ * [7] silu(gate)*up transposed, bf16 [I, ld]; ld = R_max rounded up to a multiple of 8
+ * (the weight-gradient GEMMs contract over the rows and read the copies in which the row
+ * index is contiguous; columns >= R are not read).
+ * `offsets` is a HOST array of 8. */
 int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets);
 
 /* ---- diagnostics ---------------------------------------------------------- */

@@ -169,7 +169,7 @@ def skipffn_backward_workspace_bytes(R_max, C, I) -> int:
 
 
 def skipffn_saved_layout(R_max, C, I):
-    arr = (c_size_t * 7)()
+    arr = (c_size_t * 8)()
     _check(lib().skipffn_saved_layout(R_max, C, I, arr), "skipffn_saved_layout")
     return list(arr)
 
@@ -347,4 +347,6 @@ class SkipFFNBuffers:
             "H": sect(off[5], R * I * 2, torch.bfloat16, (R, I)),
             "xnT": sect(off[6], C * ((self.R_max + 7) // 8 * 8) * 2, torch.bfloat16,
                         (C, (self.R_max + 7) // 8 * 8)),
+            "HT": sect(off[7], I * ((self.R_max + 7) // 8 * 8) * 2, torch.bfloat16,
+                       (I, (self.R_max + 7) // 8 * 8)),
         }

@@ -210,7 +210,7 @@ size_t skipffn_saved_bytes(int64_t R_max, int64_t C, int64_t I) {
 int skipffn_saved_layout(int64_t R_max, int64_t C, int64_t I, size_t* offsets) {
     if (R_max < 0 || C <= 0 || I <= 0 || offsets == nullptr) return SKIPFFN_EINVAL;
     SavedLayout L = saved_layout(R_max, C, I);
-    for (int i = 0; i < 7; ++i) offsets[i] = L.off[i];
+    for (int i = 0; i < 8; ++i) offsets[i] = L.off[i];
     return SKIPFFN_OK;
 }
 size_t skipffn_forward_workspace_bytes(int64_t R_max, int64_t C, int64_t I, int has_saved) {
@@ -262,7 +262,7 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
 
     FwdWs W = fwd_ws(Rb, C, I, saved != nullptr, num_cus());
     char* ws = static_cast<char*>(workspace);
-    bf16_t *xrows = nullptr, *xn, *xnT = nullptr, *G = nullptr, *U = nullptr, *H;
+    bf16_t *xrows = nullptr, *xn, *xnT = nullptr, *G = nullptr, *U = nullptr, *H, *HT = nullptr;
     float* rstd;
     if (saved != nullptr) {
         SavedLayout L = saved_layout(Rb, C, I);
@@ -274,6 +274,7 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
         U = reinterpret_cast<bf16_t*>(sv + L.off[4]);
         H = reinterpret_cast<bf16_t*>(sv + L.off[5]);
         xnT = reinterpret_cast<bf16_t*>(sv + L.off[6]);
+        HT = reinterpret_cast<bf16_t*>(sv + L.off[7]);
     } else {
         xn = reinterpret_cast<bf16_t*>(ws + W.xn);
         rstd = reinterpret_cast<float*>(ws + W.rstd);
@@ -310,11 +311,16 @@ int skipffn_forward(int64_t T, int64_t C, int64_t I, float eps, const void* hidd
             e = launch_gemm(true, true, EPI_PARTIAL_GU, a, s);
             if (e == hipSuccess)
                 e = launch_swiglu_reduce(a.partial, gu_splits, (int)Rb, r_dev, (int)I, a.tiles_n * BN, H, G, U, s);
+            profile_mark_end(KC_GEMM_GATE_UP, s);
+            // few rows: the K-contiguous copy of H for the dW_down GEMM comes from a copy kernel
+            if (e == hipSuccess && HT != nullptr)
+                e = launch_gather_transpose(H, (int)I, nullptr, (int)Rb, r_dev, nullptr, HT, (int)ld_transposed(Rb), s);
         } else {
             a.narrow = narrow_rows(Rb) ? 1 : 0;
+            a.outT0 = HT; a.ldt = (int)ld_transposed(Rb);     // written by the epilogue when training
             e = launch_gemm(true, true, EPI_SWIGLU, a, s);
+            profile_mark_end(KC_GEMM_GATE_UP, s);
         }
-        profile_mark_end(KC_GEMM_GATE_UP, s);
         if (e != hipSuccess) return hip_fail(e);
     }
 
@@ -411,12 +417,13 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
     SavedLayout L = saved_layout(Rb, C, I);
     const char* sv = static_cast<const char*>(saved);
     const bf16_t* xrows = reinterpret_cast<const bf16_t*>(sv + L.off[0]);
-    // L.off[1] (the normalised rows, row-major) is not read here: the weight-gradient GEMMs take the transposed copy
+    // L.off[1] and L.off[5] (the normalised rows and silu(gate)*up, row-major) are not read here: the
+    // weight-gradient GEMMs take the transposed copies
     const float* rstd = reinterpret_cast<const float*>(sv + L.off[2]);
     const bf16_t* G = reinterpret_cast<const bf16_t*>(sv + L.off[3]);
     const bf16_t* U = reinterpret_cast<const bf16_t*>(sv + L.off[4]);
-    const bf16_t* H = reinterpret_cast<const bf16_t*>(sv + L.off[5]);
     const bf16_t* xnT = reinterpret_cast<const bf16_t*>(sv + L.off[6]);
+    const bf16_t* HT = reinterpret_cast<const bf16_t*>(sv + L.off[7]);
     BwdWs W = bwd_ws(Rb, C, I);
     char* ws = static_cast<char*>(workspace);
     bf16_t* dY = reinterpret_cast<bf16_t*>(ws + W.dy);
@@ -431,8 +438,11 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
                                 dYT, ldT, s);
     if (e != hipSuccess) return hip_fail(e);
 
-    // dH = dY * W_down fused with the SiLU*mul backward (-> dG, dU), and, in the same grid
-    // (it depends only on dY and H), dW_down [C, I] = dY^T * H
+    // dH = dY * W_down fused with the SiLU*mul backward (-> dG, dU and their transposed copies),
+    // and, in the same grid (it depends only on dY and H), dW_down [C, I] = dY^T * H with both
+    // operands in their K-contiguous (R-contiguous) copies
+    bf16_t* dGT = reinterpret_cast<bf16_t*>(ws + W.dgT);
+    bf16_t* dUT = reinterpret_cast<bf16_t*>(ws + W.duT);
     {
         GemmArgs a{};
         a.M = (int)Rb; a.N = (int)I; a.K = (int)C; a.m_dev = r_dev;
@@ -440,10 +450,11 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         a.B0 = static_cast<const bf16_t*>(w_down); a.ldb = (int)I; a.b_bytes = (uint32_t)(C * I * 2);
         a.pairs = 1; a.splits = 1;
         a.out0 = dG; a.out1 = dU; a.ldo = (int)I; a.e0 = G; a.e1 = U; a.lde = (int)I;
+        a.outT0 = dGT; a.outT1 = dUT; a.ldt = ldT;
         GemmArgs b{};
         b.M = (int)C; b.N = (int)I; b.K = (int)Rb; b.k_dev = r_dev;
         b.A0 = dYT; b.lda = ldT; b.a_bytes = (uint32_t)(C * (int64_t)ldT * 2);   // K (= R) contiguous
-        b.B0 = H; b.ldb = (int)I; b.b_bytes = (uint32_t)(Rb * I * 2);
+        b.B0 = HT; b.ldb = ldT; b.b_bytes = (uint32_t)(I * (int64_t)ldT * 2);
         b.pairs = 1; b.splits = 1;
         b.out0 = dw_down; b.ldo = (int)I; b.out_f32 = f32; b.accumulate = accum;
         profile_mark_begin(KC_GEMM_DH_DWDOWN, s);
@@ -451,18 +462,17 @@ int skipffn_backward(int64_t T, int64_t C, int64_t I, float eps, const void* gra
         profile_mark_end(KC_GEMM_DH_DWDOWN, s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn : one launch, two problems.  Each is
-    // computed as (xn^T)[C, R] * dG[R, I] -> [C, I] with the K-contiguous copy of xn as the
-    // 4-fragment operand, and written transposed by the epilogue.
+    // dW_gate [I, C] = dG^T * xn ; dW_up [I, C] = dU^T * xn : one launch, two problems sharing
+    // the B operand, every operand in its K-contiguous (R-contiguous) copy
     {
         GemmArgs a{};
-        a.M = (int)C; a.N = (int)I; a.K = (int)Rb; a.k_dev = r_dev;
-        a.A0 = xnT; a.lda = ldT; a.a_bytes = (uint32_t)(C * (int64_t)ldT * 2);
-        a.B0 = dG; a.B1 = dU; a.ldb = (int)I; a.b_bytes = (uint32_t)(Rb * I * 2);
+        a.M = (int)I; a.N = (int)C; a.K = (int)Rb; a.k_dev = r_dev;
+        a.A0 = dGT; a.A1 = dUT; a.lda = ldT; a.a_bytes = (uint32_t)(I * (int64_t)ldT * 2);
+        a.B0 = xnT; a.ldb = ldT; a.b_bytes = (uint32_t)(C * (int64_t)ldT * 2);
         a.pairs = 1; a.splits = 1; a.batch = 2;
         a.out0 = dw_gate; a.out1 = dw_up; a.ldo = (int)C; a.out_f32 = f32; a.accumulate = accum;
         profile_mark_begin(KC_GEMM_DW_GATE_UP, s);
-        e = launch_gemm(true, false, EPI_STORE_T, a, s);
+        e = launch_gemm(true, true, EPI_STORE, a, s);
         profile_mark_end(KC_GEMM_DW_GATE_UP, s);
         if (e != hipSuccess) return hip_fail(e);
     }

@@ -48,7 +48,6 @@ enum EpiKind : int {
     EPI_PARTIAL = 2,       // fp32 partial[z][M][N]
     EPI_RESID_SCATTER = 3, // out0[idx[m]][n] = bf16(res[idx[m]][n] + acc)
     EPI_SWIGLU_BWD = 4,    // acc = dH; e0=G, e1=U -> out0 = dG, out1 = dU (bf16)
-    EPI_STORE_T = 5,       // like EPI_STORE, but the result is written transposed: out0[n][m] (ldo = M extent)
     EPI_PARTIAL_GU = 6     // B as for EPI_SWIGLU, fp32 partial[z][M][tiles_n * 256]: tile tn owns columns
                            // tn*256 .. +127 (gate) and +128 .. +255 (up); the SwiGLU is applied by the reducing kernel
 };
@@ -61,10 +60,11 @@ struct GemmArgs {
     const bf16_t* B0; const bf16_t* B1; int ldb; uint32_t b_bytes;
     int pairs;                   // 1, or 2: K runs over (A0,B0) then (A1,B1)
     int splits;                  // split-K factor
-    int batch;                   // 1, or 2 independent problems: (A0 -> out0), (A1 -> out1) sharing B; for
-                                 // EPI_STORE_T (B0 -> out0), (B1 -> out1) sharing A.  pairs == 1
+    int batch;                   // 1, or 2 independent problems: (A0 -> out0), (A1 -> out1) sharing B.  pairs == 1
     int tiles_m, tiles_n;
     void* out0; void* out1; void* out2; int ldo;
+    void* outT0; void* outT1; int ldt;   // SwiGLU epilogues: transposed copies [N][ldt] of out0 (H^T), or of out0 and
+                                         // out1 (dG^T, dU^T); ldt a multiple of 8 >= the row bound; null = none
     const bf16_t* e0; const bf16_t* e1; int lde;
     const int32_t* idx;
     float* partial;              // [splits][M][N]
@@ -185,7 +185,7 @@ template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const int tn, const int z,
                                           const int kt_begin, const int kt_end, const int Meff,
                                           const int Keff) {
-    static_assert(!NARROW || (A_KC && EPI != EPI_STORE_T), "the 128-row variant takes KC A operands");
+    static_assert(!NARROW || A_KC, "the 128-row variant takes KC A operands");
     constexpr int TM = NARROW ? BM / 2 : BM;        // tile rows
     constexpr int WROWS = TM / 2;                   // rows per wave row group
     constexpr int MT = WROWS / 32;                  // MFMA tiles per wave along M
@@ -372,10 +372,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                     for (int nt = 0; nt < 2; ++nt)
                         // B fragment first: the accumulator then holds, per lane, one row m of
                         // C and four consecutive columns n per register quad (see the epilogue).
-                        // EPI_STORE_T wants the opposite (one column n, four consecutive rows m).
-                        acc[mt][nt] = (EPI == EPI_STORE_T)
-                            ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s][mt], bfr[s][nt], acc[mt][nt], 0, 0, 0)
-                            : __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][nt], af[s][mt], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][nt], af[s][mt], acc[mt][nt], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         };
         auto phase_barrier = [&]() {
@@ -428,69 +425,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         if (wm == 0) phase_barrier();                     // balances group 1's extra barrier
     }
 
-    if constexpr (EPI == EPI_STORE_T) {
-        // ---- transposed epilogue: out0[n][m] = C[m][n] ---------------------------------
-        // With the A fragment first, acc[mt][nt][r] is C[row][col] with
-        //   row = m0 + wm*128 + mt*32 + 8*(r/4) + 4*(lane/32) + r%4,  col = n0 + wn*64 + nt*32 + lane%32:
-        // a register quad is four consecutive m of one column n, i.e. 16 contiguous bytes of
-        // the transposed result.  Per pass nt all eight waves stage 128 columns n x 256 rows m
-        // (fp32) in LDS; each thread then moves row-contiguous chunks of 8.
-        constexpr int T_STRIDE = 256 * 4 + 16;
-        static_assert(128 * T_STRIDE <= GEMM_LDS_BYTES, "staging must fit in LDS");
-        const int hh = lane >> 5;
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt) {
-            if (nt) lds_barrier();                   // previous pass fully read back
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    f32x4 v = {acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2],
-                               acc[mt][nt][4 * g + 3]};
-                    const int srow = wn * 32 + (lane & 31);
-                    const int scol = wm * 128 + mt * 32 + 8 * g + 4 * hh;
-                    *reinterpret_cast<f32x4*>(smem + srow * T_STRIDE + scol * 4) = v;
-                }
-            lds_barrier();
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int cid = t + 512 * i;
-                const int r = cid >> 5, c = cid & 31;          // staged row (a column n of C), chunk
-                const int ncol = n0 + (r >> 5) * 64 + nt * 32 + (r & 31);
-                const int mrow = m0 + c * 8;
-                if (ncol >= P.N || mrow >= Meff) continue;
-                const int swap = (c >> 3) & 1;
-                const char* src = smem + r * T_STRIDE + c * 32;
-                f32x4 a = *reinterpret_cast<const f32x4*>(src + (swap ? 16 : 0));
-                f32x4 b = *reinterpret_cast<const f32x4*>(src + (swap ? 0 : 16));
-                f32x4 lo = swap ? b : a, hi = swap ? a : b;
-                const uint32_t o = (uint32_t)ncol * (uint32_t)P.ldo + (uint32_t)mrow;
-                if (P.out_f32) {
-                    f32x4* O = reinterpret_cast<f32x4*>(static_cast<float*>(P.out0) + o);
-                    if (P.accumulate) { lo += O[0]; hi += O[1]; }
-                    O[0] = lo;
-                    O[1] = hi;
-                } else {
-                    u32x4* O = reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o);
-                    float v[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    if (P.accumulate) {
-                        u32x4 old = *O;
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            v[2 * k] += bf16lo_to_f32(old[k]);
-                            v[2 * k + 1] += bf16hi_to_f32(old[k]);
-                        }
-                    }
-                    u32x4 pk;
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) pk[k] = pack_bf16x2(v[2 * k], v[2 * k + 1]);
-                    *O = pk;
-                }
-            }
-        }
-        return;
-    }
-
     // ---- epilogue --------------------------------------------------------------
     // With the B fragment as first MFMA operand, acc[mt][nt][r] is C[row][col] with
     //   row = m0 + wm*WROWS + mt*32 + lane%32        (WROWS = 128, or 64 in the 128-row variant)
@@ -498,19 +432,45 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     // i.e. each register quad r = 4g..4g+3 is four consecutive columns of one row.
     // The tile leaves through LDS (free after the main loop): per pass mt, every
     // row group (wm) dumps its 32 x 256 fp32 slice as 16-byte vectors, and after a
-    // barrier each thread takes row-contiguous chunks of 8 columns, applies the
-    // epilogue arithmetic and moves 16 bytes per global access.  Two staging
-    // buffers alternate, so one barrier per pass suffices; the barrier orders LDS traffic
-    // only, so the stores of one pass overlap the staging of the next.
+    // barrier each thread takes row-contiguous chunks of 8 columns, applies the epilogue
+    // arithmetic and moves 16 bytes per global access.  The barriers order LDS traffic only, so the stores of one pass overlap
+    // the staging of the next.
+    //
+    // The SwiGLU epilogues also leave TRANSPOSED copies of their results (H^T; dG^T and dU^T:
+    // [columns][rows], leading dimension ldt) for the weight-gradient GEMMs, which contract
+    // over the rows and read both operands with plain 16-byte LDS reads when the row index is
+    // contiguous.  A thread's packed results (pairs of columns, adjacent rows) go to an LDS
+    // buffer T[column pair][row] with one 8- or 16-byte write per column pair; after a second
+    // barrier each thread picks up 8 consecutive rows of a column pair (two 16-byte reads),
+    // separates the two columns with byte permutes and stores 16 bytes per column.
+    constexpr bool HAS_T = (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_BWD);
     constexpr int SLICE_COLS = (EPI == EPI_SWIGLU) ? 128 : 256;       // per staged matrix
     constexpr int SLICE_STRIDE = SLICE_COLS * 4 + 16;                   // bytes; +16 spreads rows over banks
     constexpr int SLICE_MATS = (EPI == EPI_SWIGLU) ? 2 : 1;             // G and U
     constexpr int SLICE_BYTES = SLICE_MATS * EPI_ROWS * SLICE_STRIDE;   // per row group
-    static_assert(4 * SLICE_BYTES <= GEMM_LDS_BYTES, "staging must fit in LDS");
+    // Staging buffers: two per row group, alternating between passes, so that one barrier per
+    // pass suffices - except for the SwiGLU backward, whose two transposition buffers leave
+    // room for one per row group only (it takes a second barrier per pass anyway).
+    constexpr int NSTAGING = (EPI == EPI_SWIGLU_BWD) ? 1 : 2;
+    constexpr int T_MATS = (EPI == EPI_SWIGLU_BWD) ? 2 : 1;
+    constexpr int T_PAIRS = SLICE_COLS / 2;                             // column pairs per row group
+    constexpr int T_ROWB = EPI_ROWS * 4 + 16;                           // bytes per column pair: 32 rows + pad
+    constexpr int T_BYTES = T_PAIRS * T_ROWB + (T_PAIRS / 4) * 16;      // per matrix and row group (skewed, see t_off)
+    constexpr int T_BASE = 2 * NSTAGING * SLICE_BYTES;
+    static_assert(T_BASE + (HAS_T ? 2 * T_MATS * T_BYTES : 0) <= GEMM_LDS_BYTES, "staging must fit in LDS");
     const int h = lane >> 5;
     const int tg = t & 255;                       // thread index inside the row group
     constexpr int CHUNKS_PER_ROW = SLICE_COLS / 8;
     constexpr int CHUNKS_PER_THREAD = EPI_ROWS * CHUNKS_PER_ROW / 256;
+    // chunk i of this thread: column chunk cc, row rbase + i * RSTEP - adjacent rows where the
+    // transposed copies want them (one wide LDS write per column pair), else rows spread over the slice
+    const int cc = tg % CHUNKS_PER_ROW;
+    constexpr int RSTEP = HAS_T ? 1 : 256 / CHUNKS_PER_ROW;
+    const int rbase = HAS_T ? (tg / CHUNKS_PER_ROW) * CHUNKS_PER_THREAD : tg / CHUNKS_PER_ROW;
+    // byte offset of (column pair cp, row r) in a transposition buffer: 16 extra bytes per four
+    // column pairs (= per chunk of 8 columns) make the writes of a wave tile all 64 banks
+    auto t_off = [&](int cp, int r) { return cp * T_ROWB + (cp >> 2) * 16 + r * 4; };
+    const bool want_t = HAS_T && P.outT0 != nullptr;
 
     // EPI_SWIGLU_BWD reads G and U next to the accumulator: those 16-byte loads are issued one
     // pass ahead (and ahead of the previous pass's stores in the in-order vmcnt queue), so
@@ -520,10 +480,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         if (EPI != EPI_SWIGLU_BWD) return;
 #pragma unroll
         for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
-            const int cid = tg + 256 * i;
-            const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
-            const int row = m0 + wm * WROWS + mt * 32 + r;
-            const int col = n0 + c * 8;
+            const int row = m0 + wm * WROWS + mt * 32 + rbase + i * RSTEP;
+            const int col = n0 + cc * 8;
             if (row >= Meff || col >= P.N) continue;
             const uint32_t o = (uint32_t)row * (uint32_t)P.ldo + (uint32_t)col;
             pre_g[mt & 1][i] = *reinterpret_cast<const u32x4*>(P.e0 + o);
@@ -534,7 +492,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        char* sbuf = smem + ((mt & 1) * 2 + wm) * SLICE_BYTES;
+        char* sbuf = smem + ((NSTAGING == 2 ? (mt & 1) * 2 : 0) + wm) * SLICE_BYTES;
         // ---- dump this wave's part of the slice
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt)
@@ -551,14 +509,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             }
         lds_barrier();
         if (mt + 1 < MT) prefetch_gu(mt + 1);
+        // packed results of this thread's chunks, kept for the transposed copies: [matrix][column pair k][row i]
+        uint32_t tpk[T_MATS][4][CHUNKS_PER_THREAD];
         // ---- row-contiguous chunks of 8 columns
 #pragma unroll
         for (int i = 0; i < CHUNKS_PER_THREAD; ++i) {
-            const int cid = tg + 256 * i;
-            const int r = cid / CHUNKS_PER_ROW, c = cid % CHUNKS_PER_ROW;
+            const int r = rbase + i * RSTEP, c = cc;
             const int row = m0 + wm * WROWS + mt * 32 + r;
             const int col = n0 + c * 8;
-            if (row >= Meff || (EPI != EPI_PARTIAL_GU && col >= P.N)) continue;
+            const bool live = row < Meff && (EPI == EPI_PARTIAL_GU || col < P.N);
+            if (HAS_T) {
+#pragma unroll
+                for (int m = 0; m < T_MATS; ++m)
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) tpk[m][k][i] = 0u;     // rows past the end: zeros in the copies
+            }
+            if (!live) continue;
             // lanes c >= 8 (mod 16) read their second half first: conflict-free 16-byte reads
             const int swap = (c >> 3) & 1;
             float v[8], w[8];
@@ -585,6 +551,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                     ph[k] = pack_bf16x2(g0 * sigmoid_f(g0) * u0, g1 * sigmoid_f(g1) * u1);
                     pg[k] = pack_bf16x2(g0, g1);
                     pu[k] = pack_bf16x2(u0, u1);
+                    if (HAS_T) tpk[0][k][i] = ph[k];
                 }
                 *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o) = ph;
                 if (P.out1 != nullptr) {
@@ -659,11 +626,61 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                     }
                     dgq[k] = pack_bf16x2(dg[0], dg[1]);
                     duq[k] = pack_bf16x2(du[0], du[1]);
+                    if (HAS_T) { tpk[0][k][i] = dgq[k]; tpk[T_MATS - 1][k][i] = duq[k]; }
                 }
                 *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out0) + o) = dgq;
                 *reinterpret_cast<u32x4*>(static_cast<bf16_t*>(P.out1) + o) = duq;
             }
         }
+        if constexpr (HAS_T) {
+            if (want_t) {
+                // ---- transposed copies: T[matrix][row group][column pair][row]
+                static_assert(CHUNKS_PER_THREAD == 2 || CHUNKS_PER_THREAD == 4, "one 8- or 16-byte write per column pair");
+#pragma unroll
+                for (int m = 0; m < T_MATS; ++m) {
+                    char* tb = smem + T_BASE + (m * 2 + wm) * T_BYTES;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        char* dst = tb + t_off(cc * 4 + k, rbase);
+                        if (CHUNKS_PER_THREAD == 4) {
+                            u32x4 q = {tpk[m][k][0], tpk[m][k][1], tpk[m][k][2], tpk[m][k][3]};
+                            *reinterpret_cast<u32x4*>(dst) = q;
+                        } else {
+                            u32x2 q = {tpk[m][k][0], tpk[m][k][1]};
+                            *reinterpret_cast<u32x2*>(dst) = q;
+                        }
+                    }
+                }
+                lds_barrier();
+                // items: (matrix, column pair, block of 8 rows); 4 row blocks per column pair
+                constexpr int ITEMS = T_MATS * T_PAIRS * 4 / 256;       // per thread
+#pragma unroll
+                for (int it = 0; it < ITEMS; ++it) {
+                    const int id = tg + 256 * it;
+                    const int m = id / (T_PAIRS * 4);
+                    const int rem = id - m * (T_PAIRS * 4);
+                    const int rb = rem & 3, cp = rem >> 2;     // four consecutive lanes: 64 contiguous bytes of one column
+                    const char* tb = smem + T_BASE + (m * 2 + wm) * T_BYTES + t_off(cp, rb * 8);
+                    const u32x4 a = *reinterpret_cast<const u32x4*>(tb);
+                    const u32x4 b = *reinterpret_cast<const u32x4*>(tb + 16);
+                    // a, b: rows rb*8 .. +7 of the column pair, low half = even column
+                    u32x4 even, odd;
+                    even[0] = __builtin_amdgcn_perm(a[1], a[0], 0x05040100u); odd[0] = __builtin_amdgcn_perm(a[1], a[0], 0x07060302u);
+                    even[1] = __builtin_amdgcn_perm(a[3], a[2], 0x05040100u); odd[1] = __builtin_amdgcn_perm(a[3], a[2], 0x07060302u);
+                    even[2] = __builtin_amdgcn_perm(b[1], b[0], 0x05040100u); odd[2] = __builtin_amdgcn_perm(b[1], b[0], 0x07060302u);
+                    even[3] = __builtin_amdgcn_perm(b[3], b[2], 0x05040100u); odd[3] = __builtin_amdgcn_perm(b[3], b[2], 0x07060302u);
+                    const int colT = n0 + 2 * cp;
+                    const int rowT = m0 + wm * WROWS + mt * 32 + rb * 8;
+                    if (rowT >= P.ldt || colT >= P.N) continue;        // ldt is a multiple of 8 >= the row bound
+                    bf16_t* base = static_cast<bf16_t*>(m == 0 ? P.outT0 : P.outT1);
+                    *reinterpret_cast<u32x4*>(base + (int64_t)colT * P.ldt + rowT) = even;
+                    if (colT + 1 < P.N) *reinterpret_cast<u32x4*>(base + (int64_t)(colT + 1) * P.ldt + rowT) = odd;
+                }
+            }
+        }
+        // a single staging buffer is dumped into again by the next pass: its readers must be done (with the
+        // transposed copies the barrier before the read-back has seen to that)
+        if (NSTAGING == 1 && !want_t && mt + 1 < MT) lds_barrier();
     }
 }
 
@@ -705,7 +722,7 @@ __device__ __forceinline__ void gemm_block(GemmArgs P, const int block, const in
     const bool second = P.batch == 2 && z >= P.splits;
     if (second) {
         z -= P.splits;
-        if (EPI == EPI_STORE_T) P.B0 = P.B1; else P.A0 = P.A1;
+        P.A0 = P.A1;
         P.out0 = P.out1;
     }
     if (tm * (NARROW ? BM / 2 : BM) >= Meff) return;    // whole block leaves together: no barrier was reached yet

@@ -20,11 +20,8 @@ hipError_t gemm_init() {
     if ((e = set_lds_limit<true, true, EPI_RESID_SCATTER, true>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_PARTIAL_GU, true>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, true, EPI_PARTIAL_GU>()) != hipSuccess) return e;
-    if ((e = set_lds_limit<true, false, EPI_SWIGLU_BWD>()) != hipSuccess) return e;
     if ((e = set_lds_limit<true, false, EPI_PARTIAL>()) != hipSuccess) return e;
-    if ((e = set_lds_limit<true, false, EPI_STORE_T>()) != hipSuccess) return e;
-    if ((e = set_lds_limit<true, false, EPI_STORE>()) != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, false, EPI_STORE>),
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, true, EPI_STORE>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS_BYTES);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_streamk_kernel<true, true>),
@@ -73,7 +70,7 @@ hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s
     const int n0 = (real0 + 7) / 8 * 8;
     const int n1 = a1.tiles_m * a1.tiles_n * a1.splits * a1.batch;
     if (real0 <= 0 || n1 <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, false, EPI_STORE>),
+    hipLaunchKernelGGL((gemm_bf16_dual_kernel<true, false, EPI_SWIGLU_BWD, true, true, EPI_STORE>),
                        dim3((unsigned)(n0 + n1)), dim3(GEMM_THREADS), GEMM_LDS_BYTES, s, a0, a1, n0, real0);
     return hipGetLastError();
 }
@@ -124,10 +121,7 @@ hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& a, hipStream_t s
     if (a_kc && b_kc && epi == EPI_PARTIAL_GU) return launch_one<true, true, EPI_PARTIAL_GU>(a, s);
     if (a_kc && b_kc && epi == EPI_RESID_SCATTER) return launch_one<true, true, EPI_RESID_SCATTER>(a, s);
     if (a_kc && b_kc && epi == EPI_STORE) return launch_one<true, true, EPI_STORE>(a, s);
-    if (a_kc && !b_kc && epi == EPI_SWIGLU_BWD) return launch_one<true, false, EPI_SWIGLU_BWD>(a, s);
     if (a_kc && !b_kc && epi == EPI_PARTIAL) return launch_one<true, false, EPI_PARTIAL>(a, s);
-    if (a_kc && !b_kc && epi == EPI_STORE_T) return launch_one<true, false, EPI_STORE_T>(a, s);
-    if (a_kc && !b_kc && epi == EPI_STORE) return launch_one<true, false, EPI_STORE>(a, s);
     return hipErrorInvalidValue;
 }
 

@@ -131,7 +131,7 @@ hipError_t gemm_init();   // raises the dynamic-LDS limit of every instantiation
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, GemmArgs& args, hipStream_t s);
 // two independent GEMMs in one grid (problem 0 is dispatched first)
 enum DualKind : int {
-    DUAL_DH_DWDOWN = 0    // <KC,MNC,SWIGLU_BWD> (dH -> dG, dU)  +  <KC,MNC,STORE> (dW_down = dY^T * H)
+    DUAL_DH_DWDOWN = 0    // <KC,MNC,SWIGLU_BWD> (dH -> dG, dU)  +  <KC,KC,STORE> (dW_down = dY^T * H)
 };
 hipError_t launch_gemm_dual(int which, GemmArgs& a0, GemmArgs& a1, hipStream_t s);
 // balanced split-K GEMM into fp32 partial slabs (EPI_PARTIAL): nbg workgroups per n-tile group

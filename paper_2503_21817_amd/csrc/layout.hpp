@@ -110,7 +110,7 @@ inline size_t gate_up_partial_bytes(int64_t R, int64_t C, int64_t I, int ncu) {
 
 inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
 
-struct SavedLayout { size_t off[7]; size_t total; };
+struct SavedLayout { size_t off[8]; size_t total; };
 inline SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
     SavedLayout L;
     size_t o = 0;
@@ -121,6 +121,7 @@ inline SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {
     L.off[4] = o; o += align_up((size_t)R * I * 2);
     L.off[5] = o; o += align_up((size_t)R * I * 2);
     L.off[6] = o; o += align_up((size_t)C * ld_transposed(R) * 2);
+    L.off[7] = o; o += align_up((size_t)I * ld_transposed(R) * 2);
     L.total = o;
     return L;
 }
@@ -141,13 +142,15 @@ inline FwdWs fwd_ws(int64_t R, int64_t C, int64_t I, bool has_saved, int ncu) {
     return w;
 }
 
-struct BwdWs { size_t dy, dyT, dg, du, partial, gainp, status, total; };
+struct BwdWs { size_t dy, dyT, dg, du, dgT, duT, partial, gainp, status, total; };
 inline BwdWs bwd_ws(int64_t R, int64_t C, int64_t I) {
     BwdWs w; size_t o = 0;
     w.dy = o; o += align_up((size_t)R * C * 2);
     w.dyT = o; o += align_up((size_t)C * ld_transposed(R) * 2);
     w.dg = o; o += align_up((size_t)R * I * 2);
     w.du = o; o += align_up((size_t)R * I * 2);
+    w.dgT = o; o += align_up((size_t)I * ld_transposed(R) * 2);
+    w.duT = o; o += align_up((size_t)I * ld_transposed(R) * 2);
     w.partial = o; o += align_up((size_t)kMaxSplits * R * C * 4);
     w.gainp = o; o += align_up(gain_partial_bytes(R, C));
     w.status = o; o += 256;              // verdict of SKIPFFN_FLAG_VALIDATE_IDX

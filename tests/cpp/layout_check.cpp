@@ -40,10 +40,11 @@ int main() {
                     const size_t unit = 256;
                     // ---- saved
                     const SavedLayout L = saved_layout(R, C, I);
-                    const size_t need[7] = {(size_t)R * C * 2, (size_t)R * C * 2, (size_t)R * 4, (size_t)R * I * 2,
-                                            (size_t)R * I * 2, (size_t)R * I * 2, (size_t)C * ld_transposed(R) * 2};
+                    const size_t need[8] = {(size_t)R * C * 2, (size_t)R * C * 2, (size_t)R * 4, (size_t)R * I * 2,
+                                            (size_t)R * I * 2, (size_t)R * I * 2, (size_t)C * ld_transposed(R) * 2,
+                                            (size_t)I * ld_transposed(R) * 2};
                     std::vector<unsigned char> map(L.total / unit + 2, 0);
-                    for (int k = 0; k < 7; ++k) {
+                    for (int k = 0; k < 8; ++k) {
                         if (L.off[k] % 256) return fail("saved section not aligned", R, C, I, ncu);
                         if (L.off[k] + need[k] > L.total) return fail("saved section past the end", R, C, I, ncu);
                         if (!paint(map, L.off[k], need[k], unit)) return fail("saved sections overlap", R, C, I, ncu);
@@ -71,10 +72,11 @@ int main() {
                     {
                         const BwdWs W = bwd_ws(R, C, I);
                         std::vector<unsigned char> m3(W.total / unit + 2, 0);
-                        const size_t offs[7] = {W.dy, W.dyT, W.dg, W.du, W.partial, W.gainp, W.status};
-                        const size_t sz[7] = {(size_t)R * C * 2, (size_t)C * ld_transposed(R) * 2, (size_t)R * I * 2, (size_t)R * I * 2,
+                        const size_t offs[9] = {W.dy, W.dyT, W.dg, W.du, W.dgT, W.duT, W.partial, W.gainp, W.status};
+                        const size_t sz[9] = {(size_t)R * C * 2, (size_t)C * ld_transposed(R) * 2, (size_t)R * I * 2, (size_t)R * I * 2,
+                                              (size_t)I * ld_transposed(R) * 2, (size_t)I * ld_transposed(R) * 2,
                                               (size_t)kMaxSplits * R * C * 4, gain_partial_bytes(R, C), 8};
-                        for (int k = 0; k < 7; ++k) {
+                        for (int k = 0; k < 9; ++k) {
                             if (offs[k] % 256) return fail("backward workspace section not aligned", R, C, I, ncu);
                             if (offs[k] + sz[k] > W.total) return fail("backward workspace section past the end", R, C, I, ncu);
                             if (!paint(m3, offs[k], sz[k], unit)) return fail("backward workspace sections overlap", R, C, I, ncu);

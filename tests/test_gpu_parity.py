@@ -121,6 +121,10 @@ def test_forward_stage_by_stage(w, gain):
     xnT = bits_of(sv["xnT"])
     assert np.array_equal(xnT[:, :R], bits_of(sv["xn"]).T)
     assert not xnT[:, R:].any()
+    # so is the transposed copy of silu(gate) * up that the gate/up epilogue (or, with few rows, a copy kernel) leaves
+    HT = bits_of(sv["HT"])
+    assert np.array_equal(HT[:, :R], bits_of(sv["H"]).T)
+    assert not HT[:, R:].any()
     got = bits_of(out)
     skipped = p.mask != 0
     assert np.array_equal(got[skipped], p.hidden[skipped])      # bitwise passthrough
