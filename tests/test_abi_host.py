@@ -97,6 +97,17 @@ def test_forward_rejects_bad_arguments_on_the_host():
     assert fwd(flags=0x20) == B.EUNSUPPORTED
 
 
+def test_compact_static_rejects_bad_arguments_on_the_host():
+    c = B.lib().skipffn_compact_static        # skip_mask, T, idx, num_retained, pos, stream
+    lim = B.skipffn_compact_static_max_tokens()
+    assert lim == 2 ** 28
+    assert c(FAKE, lim + 1, FAKE, FAKE, None, None) == B.ESHAPE       # beyond the built-in scratch
+    assert c(FAKE, -1, FAKE, FAKE, None, None) == B.EINVAL
+    assert c(FAKE, 10, FAKE, None, None, None) == B.EINVAL           # no count output
+    assert c(ODD, 10, FAKE, FAKE, None, None) == B.EINVAL
+    assert c(FAKE, 10, None, FAKE, None, None) == B.EINVAL
+
+
 def test_validate_idx_rejects_bad_arguments_on_the_host():
     v = B.lib().skipffn_validate_idx          # idx, R, num_retained, T, status, stream
     assert v(FAKE, 4, None, -1, FAKE, None) == B.EINVAL
