@@ -34,50 +34,70 @@ __device__ __forceinline__ int lanes_below(uint64_t m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
 }
 
+// A wave walks its range 1024 tokens at a time: the four 4-byte mask loads of a lane are issued
+// together (the walk is bound by load latency, not by the ballots), then the four 256-token
+// slabs are ranked one after the other.
+constexpr int CP_UNROLL = 4;
+
 // number of retained tokens in [begin, end) - one wave
 __device__ int wave_count(const uint8_t* mask, int64_t begin, int64_t end, int lane) {
     int total = 0;
-    for (int64_t base = begin; base < end; base += 256) {
-        int64_t tok = base + 4 * lane;
-        uint32_t w = tok < end ? load_mask4(mask, tok, end) : 0x01010101u;
+    for (int64_t base = begin; base < end; base += 256 * CP_UNROLL) {
+        uint32_t w[CP_UNROLL];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            bool keep = ((w >> (8 * j)) & 0xffu) == 0u;
-            total += __popcll(__ballot(keep));
+        for (int q = 0; q < CP_UNROLL; ++q) {
+            const int64_t tok = base + 256 * q + 4 * lane;
+            w[q] = tok < end ? load_mask4(mask, tok, end) : 0x01010101u;
         }
+#pragma unroll
+        for (int q = 0; q < CP_UNROLL; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                bool keep = ((w[q] >> (8 * j)) & 0xffu) == 0u;
+                total += __popcll(__ballot(keep));
+            }
     }
     return total;   // uniform over the wave
 }
 
 __device__ void wave_write(const uint8_t* mask, int64_t begin, int64_t end, int lane,
                            int out_base, int32_t* idx, int32_t* pos) {
-    for (int64_t base = begin; base < end; base += 256) {
-        int64_t tok = base + 4 * lane;
-        uint32_t w = tok < end ? load_mask4(mask, tok, end) : 0x01010101u;
-        bool keep[4];
-        int rank = 0, slab = 0;
+    for (int64_t base = begin; base < end; base += 256 * CP_UNROLL) {
+        uint32_t wq[CP_UNROLL];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            keep[j] = ((w >> (8 * j)) & 0xffu) == 0u;
-            uint64_t m = __ballot(keep[j]);
-            rank += lanes_below(m);       // kept tokens of lower lanes at byte j
-            slab += __popcll(m);
+        for (int q = 0; q < CP_UNROLL; ++q) {
+            const int64_t tok = base + 256 * q + 4 * lane;
+            wq[q] = tok < end ? load_mask4(mask, tok, end) : 0x01010101u;
         }
-        // tokens of lower lanes at ANY byte position precede this lane's tokens
-        int r = out_base + rank;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (tok + j < end) {
-                if (keep[j]) {
-                    idx[r] = (int32_t)(tok + j);
-                    if (pos) pos[tok + j] = r;
-                    ++r;
-                } else if (pos) {
-                    pos[tok + j] = -1;
+        for (int q = 0; q < CP_UNROLL; ++q) {
+            const int64_t tok = base + 256 * q + 4 * lane;
+            const uint32_t w = wq[q];
+            bool keep[4];
+            int rank = 0, slab = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                keep[j] = ((w >> (8 * j)) & 0xffu) == 0u;
+                uint64_t m = __ballot(keep[j]);
+                rank += lanes_below(m);       // kept tokens of lower lanes at byte j
+                slab += __popcll(m);
+            }
+            // tokens of lower lanes at ANY byte position precede this lane's tokens
+            int r = out_base + rank;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (tok + j < end) {
+                    if (keep[j]) {
+                        idx[r] = (int32_t)(tok + j);
+                        if (pos) pos[tok + j] = r;
+                        ++r;
+                    } else if (pos) {
+                        pos[tok + j] = -1;
+                    }
                 }
             }
+            out_base += slab;
         }
-        out_base += slab;
     }
 }
 
