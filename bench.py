@@ -504,7 +504,7 @@ def mfma_probe(torch, B, random_operands, iters, steps, warmup, blocks=512):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
-    flops = blocks * 4 * iters * 8 * 32768.0
+    flops = blocks * 4 * iters * 32 * 16384.0
     c = clocks.view(blocks, 2).double()
     ghz = float((c[:, 0].sum() / c[:, 1].sum()).item()) * 0.1       # cycles per 10 ns tick
     return {"operands": "random bf16" if random_operands else "constant 1.0",
@@ -519,7 +519,7 @@ def mfma_sweep(torch, B, args):
     rows = [mfma_probe(torch, B, r, 20000, args.steps, args.warmup) for r in (0, 1)]
     return {"metric": "register-only MFMA loop", "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
             "warmup": args.warmup, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": "512 workgroups x 4 wavefronts x 160000 v_mfma_f32_32x32x16_bf16"},
+            "config": {"workload": "512 workgroups x 4 wavefronts x 640000 v_mfma_f32_16x16x32_bf16"},
             "sweep": rows}
 
 

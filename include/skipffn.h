@@ -295,9 +295,9 @@ int skipffn_last_hip_error(void);     /* hipError_t of the last SKIPFFN_EHIP on 
 int skipffn_version(void);            /* major * 10000 + minor * 100 + patch */
 
 /* Measurement aid, not part of the method: a register-only loop of independent
- * v_mfma_f32_32x32x16_bf16 (no memory traffic), i.e. what the matrix cores of the chip in hand
+ * v_mfma_f32_16x16x32_bf16 (no memory traffic), i.e. what the matrix cores of the chip in hand
  * sustain - the ceiling bench.py quotes next to the published peak.  `blocks` workgroups of 4
- * wavefronts issue iters * 8 MFMAs per wavefront (32768 FLOP each); operands are the constant
+ * wavefronts issue iters * 32 MFMAs per wavefront (16384 FLOP each); operands are the constant
  * 1.0 or, with random_operands != 0, pseudo-random bf16 values (the clock a power-capped chip
  * holds depends on the data).
  *   out     f32 [blocks * 256] device OUT (keeps the arithmetic alive)

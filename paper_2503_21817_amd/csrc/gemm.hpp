@@ -2,8 +2,10 @@
 //
 // One workgroup = 512 threads = 8 wavefronts (2 per SIMD) computes a 256 x 256
 // tile of C = A * B with fp32 accumulation, stepping K in slabs of 64.  Waves
-// are arranged 2 (M) x 4 (N); each owns 128 x 64 = 4 x 2 MFMA tiles of
-// v_mfma_f32_32x32x16_bf16 (128 accumulator registers).
+// are arranged 2 (M) x 4 (N); each owns 128 x 64 = 8 x 4 MFMA tiles of
+// v_mfma_f32_16x16x32_bf16 (128 accumulator registers).  The chip runs these loops at
+// its power limit, and the 16x16x32 form spends less energy per FLOP than 32x32x16 (half
+// the accumulator traffic): a register-only loop of it sustains 15-19 % more FLOP/s.
 //
 // Operand layouts in global memory (all row-major, as PyTorch stores them):
 //   "KC"  : [rows][K]   - the contraction index is contiguous
@@ -12,7 +14,7 @@
 // staging, no ds_write) and with no transposition: KC tiles are read back with
 // ds_read_b128 (8 consecutive k per lane), MNC tiles with the transposing
 // ds_read_b64_tr_b16 of gfx950, which hands each lane 4 consecutive k for its own
-// column.  XOR swizzles, applied on the global-address side of the direct loads,
+// column (two of them make the 8 consecutive k of an MFMA operand register set).  XOR swizzles, applied on the global-address side of the direct loads,
 // keep both read patterns free of LDS bank conflicts.
 //
 // LDS (160 KB) holds a ring of 2 A slabs and 3 B slabs of 256 x 64 (32 KB each):
@@ -27,6 +29,8 @@
 // tails) read zeros, so no shape restriction beyond "dimensions are multiples
 // of 8 elements where they are contiguous" is needed.
 #pragma once
+
+#include <utility>
 
 #include "common.hpp"
 #include "layout.hpp"
@@ -91,46 +95,62 @@ __device__ __forceinline__ uint32_t kc_off(int row, int chunk) {
     return (uint32_t)(row * 128 + (((chunk) ^ ((row >> 1) & 7)) << 4));
 }
 // MNC tile: 64 k-rows x 256 columns, 512 B per k-row, 32-byte chunk c stored at
-// c ^ (2 * (krow & 3)): the 4 k-rows x 64 B that 32 lanes of a transposing read
-// touch land in 8 distinct 32-byte slots of the 256-byte bank window.
+// c ^ mnc_swz(krow).  The 32 lanes a transposing read processes at a time are two groups of
+// 16, each touching 4 consecutive k-rows x 32 B of the same logical chunk, the groups 8 k-rows
+// apart: bits 0-1 and bit 3 of the k-row put those eight pieces into the eight distinct
+// 32-byte slots of the 256-byte bank window.
+__device__ __forceinline__ int mnc_swz(int krow) { return ((krow & 3) << 1) | ((krow >> 3) & 1); }
 __device__ __forceinline__ uint32_t mnc_off(int krow, int c32, int within) {
-    return (uint32_t)(krow * 512 + (((c32) ^ ((krow & 3) << 1)) << 5) + within);
+    return (uint32_t)(krow * 512 + (((c32) ^ mnc_swz(krow)) << 5) + within);
 }
 
-// ks = 0..3: the four k-steps of 16 inside a slab
-__device__ __forceinline__ bf16x8 lds_frag_kc(const char* tile, int row_base, int ks, int lane) {
-    int row = row_base + (lane & 31);
-    int chunk = 2 * ks + (lane >> 5);
-    u32x4 v = *reinterpret_cast<const u32x4*>(tile + kc_off(row, chunk));
+// One operand register set of v_mfma_f32_16x16x32_bf16: lane l holds row (or column) l % 16 of
+// the 16-row fragment and the 8 consecutive k starting at 8 * (l / 16).  With ks = 0, 1 the two
+// k-steps of 32 inside a slab, a KC fragment is the 16 bytes at kc_off(row_base + l % 16,
+// 4 * ks + l / 16); an MNC fragment two transposing reads at mnc_off(32 * ks + 8 * (l / 16) +
+// (l % 16) / 4 {+ 4}, col_base / 16, 8 * (l % 4)).  Fragments 16 rows (columns) apart differ by a
+// constant in the KC tile (+2048 bytes) and by an XOR of bits 5-6 in the MNC tile; the two k-steps
+// differ by a per-lane amount in the KC tile (the swizzle) and by +16384 bytes in the MNC tile.
+
+// The fragment reads of the main loop are issued through inline assembly, with the address
+// split into one per-lane register and an immediate offset.  Two reasons: while a wave issues
+// v_mfma_f32_16x16x32 back to back, every vector ALU instruction of the other wave on its SIMD
+// takes about twice as long to issue (measured: 48 dependent VALU operations 264 cycles next to
+// an idle wave, 343 next to 32x32x16 MFMAs, 478 next to 16x16x32 MFMAs; LDS reads and buffer
+// loads are not slowed), so a memory phase must spend as few VALU instructions on addresses as
+// possible; and for the builtin form of the transposing read the compiler cannot tell that it
+// does not alias the direct-to-LDS loads in flight and puts s_waitcnt vmcnt(0) in front of it,
+// which would serialise the whole load pipeline.  The assembly form is invisible to the
+// compiler's wait-count insertion, so the CALLER must wait for lgkmcnt(0) before the returned
+// registers are consumed (the main loop does, at the end of every memory phase).
+template <int IMM>
+__device__ __forceinline__ bf16x8 ds_read_b128_imm(uint32_t lds_addr) {
+    static_assert(IMM >= 0 && IMM < 65536, "16-bit offset field");
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(IMM));
     return __builtin_bit_cast(bf16x8, v);
 }
-
-// The transposing read is issued through inline assembly: for the builtin form the
-// compiler cannot tell that the read does not alias the direct-to-LDS loads in flight and
-// puts s_waitcnt vmcnt(0) in front of it, which would serialise the whole load pipeline.
-// The assembly form is invisible to that analysis, so the CALLER must wait for lgkmcnt(0)
-// before the returned registers are consumed (the main loop does, at the end of every
-// memory phase).
-__device__ __forceinline__ u32x2 ds_read_tr16_b64(uint32_t lds_addr) {
+// A group of 16 lanes addresses a 4 (k-rows) x 16 (columns) block, lane i the 8 bytes at k-row
+// i / 4, columns 4 * (i % 4) .. +3, and receives column i of it: 4 consecutive k.
+template <int IMM>
+__device__ __forceinline__ u32x2 ds_read_tr16_b64_imm(uint32_t lds_addr) {
+    static_assert(IMM >= 0 && IMM < 65536, "16-bit offset field");
     u32x2 v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"(lds_addr));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(lds_addr), "n"(IMM));
     return v;
 }
 __device__ __forceinline__ uint32_t lds_addr_of(const char* p) {
     typedef __attribute__((address_space(3))) const char* lds_cptr;
     return (uint32_t)(uintptr_t)(lds_cptr)p;
 }
-
-__device__ __forceinline__ bf16x8 lds_frag_mnc(const char* tile, int col_base, int ks, int lane) {
-    int b = lane >> 4, i = lane & 15;
-    int krow = 16 * ks + 8 * (b >> 1) + (i >> 2);
-    int c32 = (col_base >> 4) + (b & 1);
-    int within = 8 * (i & 3);
-    const uint32_t base = lds_addr_of(tile);
-    u32x2 lo = ds_read_tr16_b64(base + mnc_off(krow, c32, within));
-    u32x2 hi = ds_read_tr16_b64(base + mnc_off(krow + 4, c32, within));
-    u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
-    return __builtin_bit_cast(bf16x8, both);
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): loop indices usable as immediates
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
 }
 
 __device__ __forceinline__ float sigmoid_f(float g) {
@@ -179,16 +199,17 @@ __device__ __forceinline__ void tile_of_block(int b, int nb, int tiles_m, int ti
 //
 // NARROW: the tile is 128 rows tall (for GEMMs with few rows: twice the workgroups per row of
 // tiles, half the MFMA work per slab, so that the loop is bound by streaming B).  The eight
-// waves keep their 2 x 4 arrangement, each owning 64 x 64 = 2 x 2 MFMA tiles; only the first
+// waves keep their 2 x 4 arrangement, each owning 64 x 64 = 4 x 4 MFMA tiles; only the first
 // 16 KB of an A stage are used.  KC A operands only.
 template <bool A_KC, bool B_KC, int EPI, bool NARROW = false>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const int tn, const int z,
                                           const int kt_begin, const int kt_end, const int Meff,
                                           const int Keff) {
-    static_assert(!NARROW || A_KC, "the 128-row variant takes KC A operands");
+    static_assert(A_KC, "the A operand of every GEMM of the block is K-contiguous");
     constexpr int TM = NARROW ? BM / 2 : BM;        // tile rows
     constexpr int WROWS = TM / 2;                   // rows per wave row group
-    constexpr int MT = WROWS / 32;                  // MFMA tiles per wave along M
+    constexpr int MT = WROWS / 32;                  // epilogue passes (32 rows per row group each)
+    constexpr int MI = WROWS / 16;                  // MFMA tiles per wave along M (4 along N)
     constexpr int A_LOADS = TM / 64;                // 1 KB regions of an A slab each wave fills
     constexpr bool GU = (EPI == EPI_SWIGLU || EPI == EPI_PARTIAL_GU);   // B tile = 128 rows of W_gate + 128 of W_up
     // The A ring: 2 stages of 32 KB, fetched one slab ahead - or, for the 128-row tile, 3 stages
@@ -225,110 +246,119 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     // fetches the chunk whose swizzled home is its own 16-byte slot.
     //   KC : region q = rows 8q..8q+7;   lane -> row 8q + l/8, chunk (l%8) ^ ((row/2)%8)
     //   MNC: region q = k-rows 2q, 2q+1; lane -> krow 2q + l/32, slot p = l%32:
-    //        32-byte chunk (p/2) ^ (2 * (krow & 3)), half p & 1
+    //        32-byte chunk (p/2) ^ mnc_swz(krow), half p & 1
     uint32_t a_goff[4], b_goff[4];     // byte offset of the lane's chunk at slab 0 (or OOB)
-    int a_kk[4], b_kk[4];              // k index (inside the slab) the validity test uses
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int q = wave * 4 + i;
-        if (A_KC) {
+        {
             const int qa = wave * A_LOADS + i;      // regions of A: wave w owns A_LOADS consecutive ones
             int row = 8 * qa + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
             int gr = m0 + row;
             a_goff[i] = gr < Meff ? (uint32_t)(((int64_t)gr * P.lda + c * 8) * 2) : kOobOffset;
-            a_kk[i] = c * 8;
-        } else {
-            int krow = 2 * q + (lane >> 5), pslot = lane & 31;
-            int c16 = 2 * ((pslot >> 1) ^ ((krow & 3) << 1)) + (pslot & 1);
-            int gc = m0 + c16 * 8;
-            a_goff[i] = gc < Meff ? (uint32_t)(((int64_t)krow * P.lda + gc) * 2) : kOobOffset;
-            a_kk[i] = krow;
         }
         if (B_KC) {
             int row = 8 * q + (lane >> 3), c = (lane & 7) ^ ((row >> 1) & 7);
             // SWIGLU: tile rows 0..127 are W_gate rows, 128..255 the same rows of W_up
             int gr = GU ? n0 + (row & 127) : n0 + row;
             b_goff[i] = gr < P.N ? (uint32_t)(((int64_t)gr * P.ldb + c * 8) * 2) : kOobOffset;
-            b_kk[i] = c * 8;
         } else {
             int krow = 2 * q + (lane >> 5), pslot = lane & 31;
-            int c16 = 2 * ((pslot >> 1) ^ ((krow & 3) << 1)) + (pslot & 1);
+            int c16 = 2 * ((pslot >> 1) ^ mnc_swz(krow)) + (pslot & 1);
             int gc = n0 + c16 * 8;
             b_goff[i] = gc < P.N ? (uint32_t)(((int64_t)krow * P.ldb + gc) * 2) : kOobOffset;
-            b_kk[i] = krow;
         }
     }
     typedef __attribute__((address_space(3))) void* lds_void_ptr;
-    // issue load i (0..3) of this wave's share of A slab j / B slab j (0-based inside this
-    // block's K range)
-    // The slab step is uniform.  It can travel in the scalar offset of the buffer load, the
-    // per-lane offset staying the loop-invariant a_goff / b_goff (an invalid row keeps
-    // kOobOffset, which stays out of range with any step added; only a slab that reaches past
-    // K masks lanes individually), or be added per lane.  Measured: the scalar form costs the
-    // KC/KC loop 20 % more cycles per slab, but makes the dH + dW_down grid 1.5-2 % faster - so it
-    // is used for exactly those two instantiations.
-    constexpr bool SCALAR_STEP = !B_KC && (EPI == EPI_SWIGLU_BWD || EPI == EPI_STORE);
-    auto gload_a1 = [&](int j, int i) {
+    // Issue this wave's share of A slab j / B slab j (0-based inside this block's K range).
+    // The slab step is uniform and travels in the scalar offset of the buffer load; the per-lane
+    // offset stays the loop-invariant a_goff / b_goff (an invalid row keeps kOobOffset: the range
+    // check looks at the per-lane offset alone), so a slab that lies inside K costs no vector ALU
+    // instruction at all.  Only a slab that reaches past K (the last one of a K that is no
+    // multiple of 64) masks lanes individually; the empty assembly statements keep the compiler
+    // from merging the two forms into one load with selected operands.
+    auto gload_a = [&](int j) {
         const int kt = kt_begin + j;
         const int pair = kt >= ktiles_pair ? 1 : 0;
         const int kg = (kt - pair * ktiles_pair) * BK;  // k offset inside the pair
         __amdgpu_buffer_rsrc_t src = pair ? rA1 : rA0;
-        char* dst = smem + (j % NSA) * A_STAGE + wave * (A_LOADS * 1024) + i * 1024;
-        const uint32_t step = A_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.lda) * 2);
-        if (SCALAR_STEP && kg + BK <= Keff) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)a_goff[i], (int)step, 0, 0);
+        char* dst = smem + (j % NSA) * A_STAGE + wave * (A_LOADS * 1024);
+        const uint32_t step = (uint32_t)kg * 2u;
+        if (kg + BK <= Keff) {
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)(dst + i * 1024), 16, (int)a_goff[i], (int)step, 0, 0);
         } else {
-            uint32_t off = (a_goff[i] != kOobOffset && (kg + a_kk[i]) < Keff) ? a_goff[i] + step
-                                                                              : kOobOffset;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+            asm volatile("; K tail" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < A_LOADS; ++i) {
+                const int row = 8 * (wave * A_LOADS + i) + (lane >> 3);
+                const int kk = ((lane & 7) ^ ((row >> 1) & 7)) * 8;
+                const uint32_t off = (a_goff[i] != kOobOffset && kg + kk < Keff) ? a_goff[i] + step : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)(dst + i * 1024), 16, (int)off, 0, 0, 0);
+            }
+            asm volatile("; K tail end" ::: "memory");
         }
     };
-    auto gload_b1 = [&](int j, int i) {
+    auto gload_b = [&](int j) {
         const int kt = kt_begin + j;
         const int pair = kt >= ktiles_pair ? 1 : 0;
         const int kg = (kt - pair * ktiles_pair) * BK;
         __amdgpu_buffer_rsrc_t src = pair ? rB1 : rB0;
         if (GU) src = wave >= 4 ? rB1 : rB0;   // regions 16.. = rows 128..
-        char* dst = smem + B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096 + i * 1024;
+        char* dst = smem + B_BASE + (j % NSTAGE_B) * OPER_BYTES + wave * 4096;
         const uint32_t step = B_KC ? (uint32_t)kg * 2u : (uint32_t)(((int64_t)kg * P.ldb) * 2);
-        if (SCALAR_STEP && kg + BK <= Keff) {
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)b_goff[i], (int)step, 0, 0);
+        if (kg + BK <= Keff) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)(dst + i * 1024), 16, (int)b_goff[i], (int)step, 0, 0);
         } else {
-            uint32_t off = (b_goff[i] != kOobOffset && (kg + b_kk[i]) < Keff) ? b_goff[i] + step
-                                                                              : kOobOffset;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)dst, 16, (int)off, 0, 0, 0);
+            asm volatile("; K tail" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int kk;
+                if (B_KC) {
+                    const int row = 8 * (wave * 4 + i) + (lane >> 3);
+                    kk = ((lane & 7) ^ ((row >> 1) & 7)) * 8;
+                } else {
+                    kk = 2 * (wave * 4 + i) + (lane >> 5);
+                }
+                const uint32_t off = (b_goff[i] != kOobOffset && kg + kk < Keff) ? b_goff[i] + step : kOobOffset;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(src, (lds_void_ptr)(dst + i * 1024), 16, (int)off, 0, 0, 0);
+            }
+            asm volatile("; K tail end" ::: "memory");
         }
     };
-    auto gload_a = [&](int j) {
-#pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) gload_a1(j, i);
-    };
-    auto gload_b = [&](int j) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) gload_b1(j, i);
-    };
 
-    f32x16 acc[MT][2];
+    f32x4 acc[MI][4];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int ni = 0; ni < 4; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0.0f;
+            for (int r = 0; r < 4; ++r) acc[mi][ni][r] = 0.0f;
 
-    // rows of the B tile read by this wave's two n-tiles
-    int b_rowbase[2];
-    if (GU) {
-        b_rowbase[0] = wn * 32;          // gate columns
-        b_rowbase[1] = 128 + wn * 32;    // the same columns of up
-    } else {
-        b_rowbase[0] = wn * 64;
-        b_rowbase[1] = wn * 64 + 32;
+    // Per-lane LDS offsets of this wave's fragments inside an operand stage (see the fragment
+    // layouts above): the A fragment of MFMA tile mi lies mi * 2048 bytes after a_rd[ks]; B tile
+    // ni of a KC stage b_tile_imm(ni) bytes after b_rd[ks], of an MNC stage at b_rd[ni] plus
+    // ks * 16384 (and + 2048 for its second half).
+    uint32_t a_rd[2], b_rd[B_KC ? 2 : 4];
+    // SWIGLU: 32 gate columns (n-tiles 0, 1) and the same 32 columns of up (n-tiles 2, 3), 128 tile rows on
+    const int b_row0 = GU ? wn * 32 : wn * 64;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+        a_rd[ks] = kc_off(wm * WROWS + (lane & 15), 4 * ks + (lane >> 4));
+        if (B_KC) b_rd[ks] = kc_off(b_row0 + (lane & 15), 4 * ks + (lane >> 4));
+    }
+    if (!B_KC) {
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni)
+            b_rd[ni] = mnc_off(8 * (lane >> 4) + ((lane & 15) >> 2), (b_row0 >> 4) + ni, 8 * (lane & 3));
     }
 
     if (nk > 0) {
         // Ping-pong schedule.  The two waves that share a SIMD (wave w and w + 4, i.e.
-        // the two row groups wm = 0, 1) run one phase apart: while one issues the 16
+        // the two row groups wm = 0, 1) run one phase apart: while one issues the 32
         // MFMAs of a half slab ("compute phase"), the other reads the fragments of
         // its next half slab from LDS ("memory phase").  Phases are delimited by
         // workgroup barriers; group 1 takes one extra barrier before the loop and
@@ -346,33 +376,37 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         // A(j-1), B(j-1)) were last read in phase p-1.  Before the barrier that ends
         // phase p+3 every wave waits until only its B(j+2) loads may still be in
         // flight, so A(j+1) and B(j+1) are visible to all waves from phase p+4 on.
-        bf16x8 af[2][MT], bfr[2][2];
-        auto load_frags = [&](int j, int h) {
-            const char* sa = smem + (j % NSA) * A_STAGE;
-            const char* sb = smem + B_BASE + (j % NSTAGE_B) * OPER_BYTES;
-#pragma unroll
-            for (int s = 0; s < 2; ++s) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    af[s][mt] = A_KC ? lds_frag_kc(sa, wm * WROWS + mt * 32, 2 * h + s, lane)
-                                     : lds_frag_mnc(sa, wm * WROWS + mt * 32, 2 * h + s, lane);
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    bfr[s][nt] = B_KC ? lds_frag_kc(sb, b_rowbase[nt], 2 * h + s, lane)
-                                      : lds_frag_mnc(sb, b_rowbase[nt], 2 * h + s, lane);
+        bf16x8 af[MI], bfr[4];
+        const uint32_t lds0 = lds_addr_of(smem);
+        auto load_frags = [&](int j, auto ks) {
+            const uint32_t sa = lds0 + (uint32_t)((j % NSA) * A_STAGE);
+            const uint32_t sb = lds0 + (uint32_t)(B_BASE + (j % NSTAGE_B) * OPER_BYTES);
+            const uint32_t aa = a_rd[ks] + sa;
+            static_for<MI>([&](auto mi) { af[mi] = ds_read_b128_imm<mi * 2048>(aa); });
+            if constexpr (B_KC) {
+                const uint32_t ba = b_rd[ks] + sb;
+                static_for<4>([&](auto ni) {
+                    bfr[ni] = ds_read_b128_imm<GU ? (ni >> 1) * 16384 + (ni & 1) * 2048 : ni * 2048>(ba);
+                });
+            } else {
+                static_for<4>([&](auto ni) {
+                    const uint32_t ba = b_rd[ni] + sb;
+                    const u32x2 lo = ds_read_tr16_b64_imm<ks * 16384>(ba);
+                    const u32x2 hi = ds_read_tr16_b64_imm<ks * 16384 + 2048>(ba);
+                    const u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+                    bfr[ni] = __builtin_bit_cast(bf16x8, both);
+                });
             }
         };
         auto compute_phase = [&]() {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int s = 0; s < 2; ++s)
+            for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        // B fragment first: the accumulator then holds, per lane, one row m of
-                        // C and four consecutive columns n per register quad (see the epilogue).
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[s][nt], af[s][mt], acc[mt][nt], 0, 0, 0);
+                for (int ni = 0; ni < 4; ++ni)
+                    // B fragment first: the accumulator then holds, per lane, one row m of
+                    // C and four consecutive columns n (see the epilogue).
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         };
         auto phase_barrier = [&]() {
@@ -403,7 +437,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 
         for (int j = 0; j < nk; ++j) {
             // M(j,0)
-            load_frags(j, 0);
+            load_frags(j, std::integral_constant<int, 0>{});
             if (j + A_AHEAD < nk) gload_a(j + A_AHEAD);
             if (NARROW && j + 2 < nk) gload_b(j + 2);
             SKIPFFN_WAIT_LGKMCNT0();
@@ -412,7 +446,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             compute_phase();
             phase_barrier();
             // M(j,1)
-            load_frags(j, 1);
+            load_frags(j, std::integral_constant<int, 1>{});
             if (!NARROW && j + 2 < nk) gload_b(j + 2);
             if (wm == 1) wait_next_slab(j);
             SKIPFFN_WAIT_LGKMCNT0();
@@ -426,12 +460,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     }
 
     // ---- epilogue --------------------------------------------------------------
-    // With the B fragment as first MFMA operand, acc[mt][nt][r] is C[row][col] with
-    //   row = m0 + wm*WROWS + mt*32 + lane%32        (WROWS = 128, or 64 in the 128-row variant)
-    //   col = (tile column base) + nt*32 + 8*(r/4) + 4*(lane/32) + r%4
-    // i.e. each register quad r = 4g..4g+3 is four consecutive columns of one row.
+    // With the B fragment as first MFMA operand, acc[mi][ni][r] is C[row][col] with
+    //   row = m0 + wm*WROWS + mi*16 + lane%16        (WROWS = 128, or 64 in the 128-row variant)
+    //   col = (tile column base) + ni*16 + 4*(lane/16) + r
+    // i.e. the four registers of an MFMA tile are four consecutive columns of one row.
     // The tile leaves through LDS (free after the main loop): per pass mt, every
-    // row group (wm) dumps its 32 x 256 fp32 slice as 16-byte vectors, and after a
+    // row group (wm) dumps its 32 x 256 fp32 slice (MFMA tile rows 2mt, 2mt+1) as 16-byte vectors, and after a
     // barrier each thread takes row-contiguous chunks of 8 columns, applies the epilogue
     // arithmetic and moves 16 bytes per global access.  The barriers order LDS traffic only, so the stores of one pass overlap
     // the staging of the next.
@@ -458,7 +492,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
     constexpr int T_BYTES = T_PAIRS * T_ROWB + (T_PAIRS / 4) * 16;      // per matrix and row group (skewed, see t_off)
     constexpr int T_BASE = 2 * NSTAGING * SLICE_BYTES;
     static_assert(T_BASE + (HAS_T ? 2 * T_MATS * T_BYTES : 0) <= GEMM_LDS_BYTES, "staging must fit in LDS");
-    const int h = lane >> 5;
+    const int cq = lane >> 4;                     // column quad of this lane inside an MFMA tile
     const int tg = t & 255;                       // thread index inside the row group
     constexpr int CHUNKS_PER_ROW = SLICE_COLS / 8;
     constexpr int CHUNKS_PER_THREAD = EPI_ROWS * CHUNKS_PER_ROW / 256;
@@ -495,17 +529,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         char* sbuf = smem + ((NSTAGING == 2 ? (mt & 1) * 2 : 0) + wm) * SLICE_BYTES;
         // ---- dump this wave's part of the slice
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 v = {acc[mt][nt][4 * g], acc[mt][nt][4 * g + 1], acc[mt][nt][4 * g + 2],
-                           acc[mt][nt][4 * g + 3]};
+            for (int ni = 0; ni < 4; ++ni) {
+                const f32x4 v = acc[2 * mt + s2][ni];
                 int col, mat;
-                if (EPI == EPI_SWIGLU)          { mat = nt; col = wn * 32 + 8 * g + 4 * h; }
-                else if (EPI == EPI_PARTIAL_GU) { mat = 0;  col = nt * 128 + wn * 32 + 8 * g + 4 * h; }
-                else                            { mat = 0;  col = wn * 64 + nt * 32 + 8 * g + 4 * h; }
+                if (EPI == EPI_SWIGLU)          { mat = ni >> 1; col = wn * 32 + (ni & 1) * 16 + 4 * cq; }
+                else if (EPI == EPI_PARTIAL_GU) { mat = 0;  col = (ni >> 1) * 128 + wn * 32 + (ni & 1) * 16 + 4 * cq; }
+                else                            { mat = 0;  col = wn * 64 + ni * 16 + 4 * cq; }
                 *reinterpret_cast<f32x4*>(sbuf + mat * EPI_ROWS * SLICE_STRIDE +
-                                          (lane & 31) * SLICE_STRIDE + col * 4) = v;
+                                          (s2 * 16 + (lane & 15)) * SLICE_STRIDE + col * 4) = v;
             }
         lds_barrier();
         if (mt + 1 < MT) prefetch_gu(mt + 1);

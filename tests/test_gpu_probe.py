@@ -13,9 +13,9 @@ def test_probe_counts_every_mfma():
     clocks = torch.zeros(2 * blocks, dtype=torch.int64, device="cuda")
     B.skipffn_probe_mfma(blocks, iters, 0, out, clocks)
     torch.cuda.synchronize()
-    # operands all 1.0: one 32x32x16 MFMA adds 16 to each accumulator element; a lane holds 16
-    # elements of each of its 8 accumulator tiles and writes their sum
-    assert torch.all(out == float(iters * 16 * 16 * 8))
+    # operands all 1.0: one 16x16x32 MFMA adds 32 to each accumulator element; a lane holds 4
+    # elements of each of its 32 accumulator tiles and writes their sum
+    assert torch.all(out == float(iters * 32 * 4 * 32))
     c = clocks.view(blocks, 2)
     assert torch.all(c > 0)
     # random operands: finite, and not all equal
