@@ -398,6 +398,55 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
                 });
             }
         };
+        // The memory phase of the steady state: the loads of this phase (slabs that exist and lie
+        // inside K: no test, no mask) spread evenly between the fragment reads.  A direct-to-LDS load
+        // holds the issuing wave until the address unit takes it (about 64 cycles with four waves
+        // loading at once); reads issued before it return meanwhile.
+        auto memory_phase_fast = [&](int j, auto ks) {
+            constexpr int KS = decltype(ks)::value;
+            constexpr int NLA = KS == 0 ? A_LOADS : 0;
+            constexpr int NLB = (NARROW ? KS == 0 : KS == 1) ? 4 : 0;
+            constexpr int NL = NLA + NLB, NR = MI + 4;
+            const uint32_t sa = lds0 + (uint32_t)((j % NSA) * A_STAGE);
+            const uint32_t sb = lds0 + (uint32_t)(B_BASE + (j % NSTAGE_B) * OPER_BYTES);
+            const uint32_t aa = a_rd[KS] + sa;
+            const uint32_t ba = B_KC ? b_rd[KS] + sb : sb;
+            // uniform parameters of the loads
+            const int kta = kt_begin + j + A_AHEAD, ktb = kt_begin + j + 2;
+            const int paira = kta >= ktiles_pair ? 1 : 0, pairb = ktb >= ktiles_pair ? 1 : 0;
+            const uint32_t stepa = (uint32_t)((kta - paira * ktiles_pair) * BK) * 2u;
+            const int kgb = (ktb - pairb * ktiles_pair) * BK;
+            const uint32_t stepb = B_KC ? (uint32_t)kgb * 2u : (uint32_t)(((int64_t)kgb * P.ldb) * 2);
+            const __amdgpu_buffer_rsrc_t srca = paira ? rA1 : rA0;
+            const __amdgpu_buffer_rsrc_t srcb = GU ? (wave >= 4 ? rB1 : rB0) : (pairb ? rB1 : rB0);
+            char* dsta = smem + ((j + A_AHEAD) % NSA) * A_STAGE + wave * (A_LOADS * 1024);
+            char* dstb = smem + B_BASE + ((j + 2) % NSTAGE_B) * OPER_BYTES + wave * 4096;
+            static_for<NR>([&](auto r) {
+                static_for<NL>([&](auto l) {
+                    if constexpr (l * NR / NL == r) {
+                        if constexpr (l < NLA)
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(srca, (lds_void_ptr)(dsta + l * 1024), 16,
+                                                                     (int)a_goff[l], (int)stepa, 0, 0);
+                        else
+                            __builtin_amdgcn_raw_ptr_buffer_load_lds(srcb, (lds_void_ptr)(dstb + (l - NLA) * 1024), 16,
+                                                                     (int)b_goff[l - NLA], (int)stepb, 0, 0);
+                    }
+                });
+                if constexpr (r < MI) {
+                    af[r] = ds_read_b128_imm<r * 2048>(aa);
+                } else if constexpr (B_KC) {
+                    constexpr int ni = r - MI;
+                    bfr[ni] = ds_read_b128_imm<GU ? (ni >> 1) * 16384 + (ni & 1) * 2048 : ni * 2048>(ba);
+                } else {
+                    constexpr int ni = r - MI;
+                    const uint32_t bn = b_rd[ni] + ba;
+                    const u32x2 lo = ds_read_tr16_b64_imm<KS * 16384>(bn);
+                    const u32x2 hi = ds_read_tr16_b64_imm<KS * 16384 + 2048>(bn);
+                    const u32x4 both = {lo[0], lo[1], hi[0], hi[1]};
+                    bfr[ni] = __builtin_bit_cast(bf16x8, both);
+                }
+            });
+        };
         auto compute_phase = [&]() {
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -435,19 +484,32 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         phase_barrier();
         if (wm == 1) phase_barrier();                     // group 1 starts one phase later
 
+        // slabs [0, kfull) of a pair lie inside K
+        const int kfull = Keff / BK;
+        auto inside_k = [&](int kt) { return (kt >= ktiles_pair ? kt - ktiles_pair : kt) < kfull; };
         for (int j = 0; j < nk; ++j) {
+            // steady state: the slabs this iteration loads exist and need no K mask
+            const bool fast = j + 2 < nk && inside_k(kt_begin + j + A_AHEAD) && inside_k(kt_begin + j + 2);
             // M(j,0)
-            load_frags(j, std::integral_constant<int, 0>{});
-            if (j + A_AHEAD < nk) gload_a(j + A_AHEAD);
-            if (NARROW && j + 2 < nk) gload_b(j + 2);
+            if (fast) {
+                memory_phase_fast(j, std::integral_constant<int, 0>{});
+            } else {
+                load_frags(j, std::integral_constant<int, 0>{});
+                if (j + A_AHEAD < nk) gload_a(j + A_AHEAD);
+                if (NARROW && j + 2 < nk) gload_b(j + 2);
+            }
             SKIPFFN_WAIT_LGKMCNT0();
             phase_barrier();
             // C(j,0)
             compute_phase();
             phase_barrier();
             // M(j,1)
-            load_frags(j, std::integral_constant<int, 1>{});
-            if (!NARROW && j + 2 < nk) gload_b(j + 2);
+            if (fast) {
+                memory_phase_fast(j, std::integral_constant<int, 1>{});
+            } else {
+                load_frags(j, std::integral_constant<int, 1>{});
+                if (!NARROW && j + 2 < nk) gload_b(j + 2);
+            }
             if (wm == 1) wait_next_slab(j);
             SKIPFFN_WAIT_LGKMCNT0();
             phase_barrier();
