@@ -452,10 +452,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-                for (int ni = 0; ni < 4; ++ni)
+                for (int nj = 0; nj < 4; ++nj) {
                     // B fragment first: the accumulator then holds, per lane, one row m of
-                    // C and four consecutive columns n (see the epilogue).
+                    // C and four consecutive columns n (see the epilogue).  Boustrophedon order:
+                    // consecutive MFMAs always share one operand register set.
+                    const int ni = (mi & 1) ? 3 - nj : nj;
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[ni], af[mi], acc[mi][ni], 0, 0, 0);
+                }
             __builtin_amdgcn_sched_barrier(0);
         };
         auto phase_barrier = [&]() {
