@@ -401,26 +401,27 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
         // The memory phase of the steady state: the loads of this phase (slabs that exist and lie
         // inside K: no test, no mask) spread evenly between the fragment reads.  A direct-to-LDS load
         // holds the issuing wave until the address unit takes it (about 64 cycles with four waves
-        // loading at once); reads issued before it return meanwhile.
-        auto memory_phase_fast = [&](int j, auto ks) {
+        // loading at once); reads issued before it return meanwhile.  While the other wave of the
+        // SIMD issues MFMAs back to back, EVERY instruction of this wave - scalar ones included -
+        // takes two to three times as long to issue (a wait of 32 cycles inserted here costs 90), so
+        // the phase carries as few instructions as possible: everything uniform about it (ring
+        // stages, the scalar offsets of the loads, the operand descriptors) is kept in registers
+        // and stepped once per slab instead of being derived from the slab index.
+        uint32_t st_rd_a = 0, st_rd_b = 0;       // LDS address of the stages slab j is read from
+        uint32_t st_ld_a = 0, st_ld_b = 0;       // LDS offset this wave loads slab j + A_AHEAD of A / slab j + 2 of B to
+        uint32_t st_step_a = 0, st_step_b = 0;   // scalar offsets of those loads
+        __amdgpu_buffer_rsrc_t st_src_a = rA0, st_src_b = rB0;
+        auto memory_phase_fast = [&](auto ks) {
             constexpr int KS = decltype(ks)::value;
             constexpr int NLA = KS == 0 ? A_LOADS : 0;
             constexpr int NLB = (NARROW ? KS == 0 : KS == 1) ? 4 : 0;
             constexpr int NL = NLA + NLB, NR = MI + 4;
-            const uint32_t sa = lds0 + (uint32_t)((j % NSA) * A_STAGE);
-            const uint32_t sb = lds0 + (uint32_t)(B_BASE + (j % NSTAGE_B) * OPER_BYTES);
-            const uint32_t aa = a_rd[KS] + sa;
-            const uint32_t ba = B_KC ? b_rd[KS] + sb : sb;
-            // uniform parameters of the loads
-            const int kta = kt_begin + j + A_AHEAD, ktb = kt_begin + j + 2;
-            const int paira = kta >= ktiles_pair ? 1 : 0, pairb = ktb >= ktiles_pair ? 1 : 0;
-            const uint32_t stepa = (uint32_t)((kta - paira * ktiles_pair) * BK) * 2u;
-            const int kgb = (ktb - pairb * ktiles_pair) * BK;
-            const uint32_t stepb = B_KC ? (uint32_t)kgb * 2u : (uint32_t)(((int64_t)kgb * P.ldb) * 2);
-            const __amdgpu_buffer_rsrc_t srca = paira ? rA1 : rA0;
-            const __amdgpu_buffer_rsrc_t srcb = GU ? (wave >= 4 ? rB1 : rB0) : (pairb ? rB1 : rB0);
-            char* dsta = smem + ((j + A_AHEAD) % NSA) * A_STAGE + wave * (A_LOADS * 1024);
-            char* dstb = smem + B_BASE + ((j + 2) % NSTAGE_B) * OPER_BYTES + wave * 4096;
+            const uint32_t aa = a_rd[KS] + st_rd_a;
+            const uint32_t ba = B_KC ? b_rd[KS] + st_rd_b : st_rd_b;
+            const uint32_t stepa = st_step_a, stepb = st_step_b;
+            const __amdgpu_buffer_rsrc_t srca = st_src_a, srcb = st_src_b;
+            char* dsta = smem + st_ld_a;
+            char* dstb = smem + st_ld_b;
             static_for<NR>([&](auto r) {
                 static_for<NL>([&](auto l) {
                     if constexpr (l * NR / NL == r) {
@@ -489,17 +490,53 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
 
         // slabs [0, kfull) of a pair lie inside K
         const int kfull = Keff / BK;
-        auto inside_k = [&](int kt) { return (kt >= ktiles_pair ? kt - ktiles_pair : kt) < kfull; };
+        const uint32_t dstep_b = B_KC ? (uint32_t)BK * 2u : (uint32_t)BK * (uint32_t)P.ldb * 2u;
+        const uint32_t rd_a_end = lds0 + NSA * A_STAGE, rd_b_end = lds0 + B_BASE + NSTAGE_B * OPER_BYTES;
+        const uint32_t ld_a_end = NSA * A_STAGE + wave * (A_LOADS * 1024);
+        const uint32_t ld_b_end = B_BASE + NSTAGE_B * OPER_BYTES + wave * 4096;
+        int fast_end = 0;                  // iterations [j, fast_end) are steady state
         for (int j = 0; j < nk; ++j) {
-            // steady state: the slabs this iteration loads exist and need no K mask
-            const bool fast = j + 2 < nk && inside_k(kt_begin + j + A_AHEAD) && inside_k(kt_begin + j + 2);
+            bool fast = j < fast_end;
+            if (!fast) {
+                // does a steady-state run start at slab j?  For `run` iterations the slabs to load
+                // (j + A_AHEAD of A, j + 2 of B) exist, lie inside K and stay in the operand pair they
+                // are in now.
+                // (the empty assembly statements pin this rarely executed arithmetic to this place and to
+                // scalar registers: derived from the loop counter, it would otherwise be hoisted to the
+                // top of every iteration)
+                int js = j;
+                asm volatile("" : "+s"(js));
+                const int kta = kt_begin + js + A_AHEAD, ktb = kt_begin + js + 2;
+                const int paira = kta >= ktiles_pair ? 1 : 0, pairb = ktb >= ktiles_pair ? 1 : 0;
+                const int ia = kta - paira * ktiles_pair, ib = ktb - pairb * ktiles_pair;
+                int run = nk - 2 - js;
+                run = run < kfull - ia ? run : kfull - ia;
+                asm volatile("" : "+s"(run));
+                run = run < kfull - ib ? run : kfull - ib;
+                asm volatile("" : "+s"(run));
+                if (run > 0) {
+                    fast = true;
+                    fast_end = js + run;
+                    st_rd_a = lds0 + (uint32_t)((js % NSA) * A_STAGE);
+                    st_rd_b = lds0 + (uint32_t)(B_BASE + (js % NSTAGE_B) * OPER_BYTES);
+                    st_ld_a = (uint32_t)(((js + A_AHEAD) % NSA) * A_STAGE + wave * (A_LOADS * 1024));
+                    st_ld_b = (uint32_t)(B_BASE + ((js + 2) % NSTAGE_B) * OPER_BYTES + wave * 4096);
+                    st_step_a = (uint32_t)(ia * BK) * 2u;
+                    st_step_b = (uint32_t)ib * dstep_b;
+                    st_src_a = paira ? rA1 : rA0;
+                    st_src_b = GU ? (wave >= 4 ? rB1 : rB0) : (pairb ? rB1 : rB0);
+                }
+            }
             // M(j,0)
             if (fast) {
-                memory_phase_fast(j, std::integral_constant<int, 0>{});
+                memory_phase_fast(std::integral_constant<int, 0>{});
             } else {
-                load_frags(j, std::integral_constant<int, 0>{});
-                if (j + A_AHEAD < nk) gload_a(j + A_AHEAD);
-                if (NARROW && j + 2 < nk) gload_b(j + 2);
+                // a slab at the end of the K range (or of a pair): loads guarded and masked
+                int js = j;
+                asm volatile("" : "+s"(js));
+                load_frags(js, std::integral_constant<int, 0>{});
+                if (js + A_AHEAD < nk) gload_a(js + A_AHEAD);
+                if (NARROW && js + 2 < nk) gload_b(js + 2);
             }
             SKIPFFN_WAIT_LGKMCNT0();
             phase_barrier();
@@ -508,10 +545,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             phase_barrier();
             // M(j,1)
             if (fast) {
-                memory_phase_fast(j, std::integral_constant<int, 1>{});
+                memory_phase_fast(std::integral_constant<int, 1>{});
             } else {
-                load_frags(j, std::integral_constant<int, 1>{});
-                if (!NARROW && j + 2 < nk) gload_b(j + 2);
+                int js = j;
+                asm volatile("" : "+s"(js));
+                load_frags(js, std::integral_constant<int, 1>{});
+                if (!NARROW && js + 2 < nk) gload_b(js + 2);
             }
             if (wm == 1) wait_next_slab(j);
             SKIPFFN_WAIT_LGKMCNT0();
@@ -519,6 +558,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& P, const int tm, const
             // C(j,1)
             compute_phase();
             if (wm == 0) wait_next_slab(j);
+            if (fast) {
+                // next slab: rotate the ring stages, step the load offsets
+                st_rd_a += A_STAGE; if (st_rd_a == rd_a_end) st_rd_a -= NSA * A_STAGE;
+                st_rd_b += OPER_BYTES; if (st_rd_b == rd_b_end) st_rd_b -= NSTAGE_B * OPER_BYTES;
+                st_ld_a += A_STAGE; if (st_ld_a == ld_a_end) st_ld_a -= NSA * A_STAGE;
+                st_ld_b += OPER_BYTES; if (st_ld_b == ld_b_end) st_ld_b -= NSTAGE_B * OPER_BYTES;
+                st_step_a += (uint32_t)BK * 2u;
+                st_step_b += dstep_b;
+            }
             phase_barrier();
         }
         if (wm == 0) phase_barrier();                     // balances group 1's extra barrier
