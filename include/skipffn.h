@@ -283,7 +283,7 @@ int skipffn_token_merge_backward(const void* grad_out, const int32_t* seg_host, 
  * offsets[0] x rows bf16 [R, C]; [1] normalised rows bf16 [R, C];
  * [2] 1/rms f32 [R]; [3] gate bf16 [R, I]; [4] up bf16 [R, I];
  * [5] silu(gate)*up bf16 [R, I]; [6] normalised rows transposed, bf16 [C, ld];
- * [7] silu(gate)*up transposed, bf16 [I, ld]; ld = R_max rounded up to a multiple of 8
+ * [7] silu(gate)*up transposed, bf16 [I, ld]; ld = R_max rounded up to a multiple of 64
  * (the weight-gradient GEMMs contract over the rows and read the copies in which the row
  * index is contiguous; columns >= R are not read).
  * `offsets` is a HOST array of 8. */

@@ -345,8 +345,8 @@ class SkipFFNBuffers:
             "G": sect(off[3], R * I * 2, torch.bfloat16, (R, I)),
             "U": sect(off[4], R * I * 2, torch.bfloat16, (R, I)),
             "H": sect(off[5], R * I * 2, torch.bfloat16, (R, I)),
-            "xnT": sect(off[6], C * ((self.R_max + 7) // 8 * 8) * 2, torch.bfloat16,
-                        (C, (self.R_max + 7) // 8 * 8)),
-            "HT": sect(off[7], I * ((self.R_max + 7) // 8 * 8) * 2, torch.bfloat16,
-                       (I, (self.R_max + 7) // 8 * 8)),
+            "xnT": sect(off[6], C * ((self.R_max + 63) // 64 * 64) * 2, torch.bfloat16,
+                        (C, (self.R_max + 63) // 64 * 64)),
+            "HT": sect(off[7], I * ((self.R_max + 63) // 64 * 64) * 2, torch.bfloat16,
+                       (I, (self.R_max + 63) // 64 * 64)),
         }

@@ -108,7 +108,10 @@ inline size_t gate_up_partial_bytes(int64_t R, int64_t C, int64_t I, int ncu) {
     return s ? (size_t)s * (size_t)rows * (size_t)tiles_n * BN * 4 : 0;
 }
 
-inline int64_t ld_transposed(int64_t R) { return (R + 7) / 8 * 8; }
+// Leading dimension of the transposed copies ([columns][rows]): rows rounded up to 64 elements, so that every
+// row of a copy starts on a 128-byte line (with a multiple of 8 only, each 128-byte piece the GEMMs load
+// straddles two lines: the weight-gradient GEMMs ran 11-23 % slower at such row counts).
+inline int64_t ld_transposed(int64_t R) { return (R + 63) / 64 * 64; }
 
 struct SavedLayout { size_t off[8]; size_t total; };
 inline SavedLayout saved_layout(int64_t R, int64_t C, int64_t I) {

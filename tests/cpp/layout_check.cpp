@@ -49,7 +49,7 @@ int main() {
                         if (L.off[k] + need[k] > L.total) return fail("saved section past the end", R, C, I, ncu);
                         if (!paint(map, L.off[k], need[k], unit)) return fail("saved sections overlap", R, C, I, ncu);
                     }
-                    if (ld_transposed(R) % 8 || ld_transposed(R) < R) return fail("transposed leading dimension", R, C, I, ncu);
+                    if (ld_transposed(R) % 64 || ld_transposed(R) < R) return fail("transposed leading dimension", R, C, I, ncu);
                     if (L.total < prev_sv) return fail("saved size decreases", R, C, I, ncu);
                     prev_sv = L.total;
                     // ---- forward workspace, with and without a saved buffer

@@ -40,8 +40,8 @@ def test_size_queries_are_monotone_and_cover_their_sections():
         sv = B.skipffn_saved_bytes(R, C, I)
         off = B.skipffn_saved_layout(R, C, I)
         assert off == sorted(off) and off[0] == 0
-        assert len(off) == 8 and sv >= off[7] + I * ((R + 7) // 8 * 8) * 2
-        assert off[7] - off[6] >= C * ((R + 7) // 8 * 8) * 2
+        assert len(off) == 8 and sv >= off[7] + I * ((R + 63) // 64 * 64) * 2
+        assert off[7] - off[6] >= C * ((R + 63) // 64 * 64) * 2
         assert off[6] - off[5] >= R * I * 2
         assert off[1] - off[0] >= R * C * 2 and off[3] - off[2] >= R * 4
         fw_inf = B.skipffn_forward_workspace_bytes(R, C, I, False)
