@@ -141,7 +141,7 @@ const char* skipffn_status_string(int status) {
 }
 
 int skipffn_last_hip_error(void) { return g_last_hip; }
-int skipffn_version(void) { return 200; }
+int skipffn_version(void) { return 20100; }   // 2.1.0: leading dimension of the transposed saved copies
 
 int skipffn_profile_begin(void) {
     std::lock_guard<std::mutex> lk(g_prof_mu);
