@@ -922,18 +922,21 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_bf16_streamk_kernel(GemmArg
     // works on ONE K range of many n-tiles (the m-tiles of an n-tile share the weight slabs,
     // the n-tiles share the activation slabs, and no XCD streams the whole K extent of the
     // activations); the remainder pieces follow.  (tn, j) = n-tile and workgroup index in its group.
+    // (With more tiles than workgroups in a group every workgroup starts with whole tiles of its own,
+    // see streamk.hpp; the order below is that of the gr tiles that are split.)
     int tn, j;
-    const int aligned_total = p.a * g * tiles_n;
+    const int gr = p.gr;
+    const int aligned_total = p.a * gr * tiles_n;
     if (b < aligned_total) {
-        const int c = b / (tiles_n * g);
-        const int r = b - c * (tiles_n * g);
-        tn = r / g;
-        j = c * g + (r - tn * g);
+        const int c = b / (tiles_n * gr);
+        const int r = b - c * (tiles_n * gr);
+        tn = r / gr;
+        j = c * gr + (r - tn * gr);
     } else {
-        const int per = nbg - p.a * g;            // workgroups per group left for the remainder
+        const int per = nbg - p.a * gr;           // workgroups per group left for the remainder
         const int r = b - aligned_total;
         tn = r / per;
-        j = p.a * g + (r - tn * per);
+        j = p.a * gr + (r - tn * per);
     }
     StreamKIter it = streamk_begin(p, j);
     StreamKSeg sg;

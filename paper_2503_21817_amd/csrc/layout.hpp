@@ -32,8 +32,8 @@ constexpr int kMaxSplitsNarrow = 16;     // few rows: small fp32 slabs, and ever
 //   splits == 1, sk_nbg == 0 : one workgroup per tile, epilogue fused
 //   splits  > 1, sk_nbg == 0 : plain split-K into `splits` fp32 slabs
 //   sk_nbg  > 0              : balanced split (gemm_bf16_streamk_kernel), sk_nbg workgroups per
-//                              n-tile group (with more m-tiles than workgroups in a group, a
-//                              workgroup walks several tiles and only boundary tiles are shared)
+//                              n-tile group (with more m-tiles than workgroups in a group, every
+//                              workgroup first runs whole tiles of its own; the rest is split)
 struct KPartition { int splits; int sk_nbg; };
 inline KPartition choose_k_partition(int tiles_m, int tiles_n, int ktiles, bool force_balanced, int ncu) {
     const int tiles = tiles_m * tiles_n;
@@ -50,14 +50,15 @@ inline KPartition choose_k_partition(int tiles_m, int tiles_n, int ktiles, bool 
     if (nbg >= 1 && tiles > 0) {
         const StreamKPlan p = streamk_plan(tiles_m, ktiles, nbg);
         if (force_balanced) return KPartition{1, nbg};
-        if (p.q >= 8) {
+        if (p.gr > 0 && p.q >= 8) {
             double slabs = 0.0;
             for (int i = 0; i < tiles_m; ++i) slabs += streamk_count(p, i);
             // an aligned chunk is one segment; a remainder piece runs one segment (with its own
-            // prologue and epilogue: about 5 slabs' worth, measured) per tile it touches
+            // prologue and epilogue: about 5 slabs' worth, measured) per tile it touches; with more
+            // tiles than workgroups in a group, whole tiles come first
             const double aligned = p.a > 0 ? p.q + 16.0 : 0.0;
             const double pieces = p.nr > 0 ? p.qr + 16.0 + 5.0 * (p.qr / p.rem) : 0.0;
-            double cost = std::max(aligned, pieces) + 0.04 * slabs * tiles_n;
+            double cost = p.full * (ktiles + 16.0) + std::max(aligned, pieces) + 0.04 * slabs * tiles_n;
             if (cost < best_cost - 1e-9) { best_cost = cost; best = KPartition{1, nbg}; }
         }
     }

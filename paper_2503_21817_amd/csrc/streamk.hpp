@@ -13,6 +13,14 @@
 //     touches.
 // Tile i of a group receives streamk_count() partial slabs: slots 0..a-1 from the aligned
 // chunks, then one or two from the remainder pieces.  The reducing kernels add exactly those.
+//
+// A group with more tiles than workgroups (g > nbg) first gives every workgroup `full` = g / nbg
+// whole tiles (workgroup j: tiles j, j + nbg, ...: one partial slab each, and the nbg tiles of a
+// round walk the K range together); the scheme above then applies to the gr = g - full * nbg tiles
+// that are left.  (Letting every workgroup walk an equal share of all g tiles end to end balances
+// just as well, but puts the workgroups of a group at different K positions: the streamed operand
+// is then fetched once per workgroup instead of once per group - measured 13-20 % slower on the
+// down and dXn GEMMs at 17 and 33 tile rows.)
 #pragma once
 
 #if defined(__HIPCC__)
@@ -23,12 +31,17 @@
 
 namespace skipffn {
 
-struct StreamKPlan { int g, kt, nbg, q, a, rem, nr, qr; };
+struct StreamKPlan { int g, kt, nbg, q, a, rem, nr, qr, full, base, gr; };
 constexpr int kStreamKMaxAligned = 6;            // at most 6 + 2 partial slabs per tile
 
 SKIPFFN_HD inline StreamKPlan streamk_plan(int g, int kt, int nbg) {
     StreamKPlan p;
     p.g = g; p.kt = kt; p.nbg = nbg;
+    p.full = g > nbg ? g / nbg : 0;
+    p.base = p.full * nbg;
+    p.gr = g - p.base;
+    g = p.gr;                                                // the split applies to these tiles
+    if (g == 0) { p.q = kt > 0 ? kt : 1; p.a = 0; p.rem = 0; p.nr = 0; p.qr = 1; return p; }
     const int q_bal = (g * kt + nbg - 1) / nbg;
     const int q_min = (kt + kStreamKMaxAligned - 1) / kStreamKMaxAligned;
     p.q = q_bal > q_min ? q_bal : q_min;
@@ -48,6 +61,8 @@ SKIPFFN_HD inline StreamKPlan streamk_plan(int g, int kt, int nbg) {
 
 // number of partial slabs tile i (0 <= i < g) of a group receives
 SKIPFFN_HD inline int streamk_count(const StreamKPlan& p, int i) {
+    if (i < p.base) return 1;
+    i -= p.base;
     int c = p.a;
     if (p.rem > 0) c += ((i + 1) * p.rem - 1) / p.qr - (i * p.rem) / p.qr + 1;
     return c;
@@ -57,38 +72,46 @@ SKIPFFN_HD inline int streamk_count(const StreamKPlan& p, int i) {
 //   StreamKIter it = streamk_begin(p, j);  StreamKSeg s;  while (streamk_next(p, it, s)) ...
 // A segment is K slabs [kb, ke) of tile i, accumulated into partial slab `slot` of that tile.
 struct StreamKSeg { int i, kb, ke, slot; };
-struct StreamKIter { int j, u, u_end; };
+struct StreamKIter { int j, u, u_end, f; };
 SKIPFFN_HD inline StreamKIter streamk_begin(const StreamKPlan& p, int j) {
     StreamKIter it;
     it.j = j;
-    if (j < p.a * p.g) {                 // aligned chunk: one pseudo-unit
+    it.f = 0;                            // whole tiles done so far
+    if (j < p.a * p.gr) {                // aligned chunk: one pseudo-unit
         it.u = 0; it.u_end = 1;
     } else {
-        const int rj = j - p.a * p.g;
+        const int rj = j - p.a * p.gr;
         if (rj >= p.nr) { it.u = 0; it.u_end = 0; return it; }
         it.u = rj * p.qr;
         it.u_end = it.u + p.qr;
-        if (it.u_end > p.g * p.rem) it.u_end = p.g * p.rem;
+        if (it.u_end > p.gr * p.rem) it.u_end = p.gr * p.rem;
     }
     return it;
 }
 SKIPFFN_HD inline bool streamk_next(const StreamKPlan& p, StreamKIter& it, StreamKSeg& s) {
+    if (it.f < p.full) {                 // a whole tile of this workgroup's own
+        s.i = it.f * p.nbg + it.j;
+        s.kb = 0; s.ke = p.kt; s.slot = 0;
+        ++it.f;
+        return true;
+    }
     if (it.u >= it.u_end) return false;
-    if (it.j < p.a * p.g) {
-        const int c = it.j / p.g;
-        s.i = it.j - c * p.g;
+    if (it.j < p.a * p.gr) {
+        const int c = it.j / p.gr;
+        s.i = p.base + it.j - c * p.gr;
         s.kb = c * p.q;
         s.ke = s.kb + p.q;
         s.slot = c;
         it.u = it.u_end;
         return true;
     }
-    const int rj = it.j - p.a * p.g;
-    s.i = it.u / p.rem;
-    const int k0 = it.u - s.i * p.rem;
+    const int rj = it.j - p.a * p.gr;
+    const int ir = it.u / p.rem;         // index among the tiles that are split
+    s.i = p.base + ir;
+    const int k0 = it.u - ir * p.rem;
     int len = p.rem - k0;
     if (len > it.u_end - it.u) len = it.u_end - it.u;
-    s.slot = p.a + rj - (s.i * p.rem) / p.qr;
+    s.slot = p.a + rj - (ir * p.rem) / p.qr;
     s.kb = p.a * p.q + k0;
     s.ke = s.kb + len;
     it.u += len;

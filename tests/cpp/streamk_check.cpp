@@ -1,7 +1,7 @@
 // Brute-force check of the balanced K split (csrc/streamk.hpp): for every (g, kt, nbg) in a
 // range, every K slab of every tile is covered exactly once, slot numbers of a tile are
 // 0..count-1 without repeats, counts stay within the partial-slab budget, and no workgroup
-// gets more than q slabs.  Prints "ok <cases>" or the first violation.
+// gets more than q slabs beyond its whole tiles.  Prints "ok <cases>" or the first violation.
 #include <cstdio>
 #include <vector>
 #include "../../paper_2503_21817_amd/csrc/streamk.hpp"
@@ -13,7 +13,8 @@ int main() {
         for (int nbg = 1; nbg <= 40; ++nbg)
             for (int kt = 1; kt <= 300; kt += (kt < 70 ? 1 : 7)) {
                 const StreamKPlan p = streamk_plan(g, kt, nbg);
-                if (p.a * g > nbg || p.a > kStreamKMaxAligned || (p.rem > 0 && (p.nr < 1 || p.a * g + p.nr > nbg)) ||
+                if (p.base + p.gr != g || p.gr < 0 || (g > nbg && p.gr >= nbg) || (g <= nbg && p.full != 0) ||
+                    p.a * p.gr > nbg || p.a > kStreamKMaxAligned || (p.rem > 0 && (p.nr < 1 || p.a * p.gr + p.nr > nbg)) ||
                     (p.rem > 0 && p.qr < p.rem)) {
                     printf("bad plan g=%d kt=%d nbg=%d: q=%d a=%d rem=%d nr=%d qr=%d\n", g, kt, nbg, p.q, p.a, p.rem, p.nr, p.qr);
                     return 1;
@@ -33,7 +34,7 @@ int main() {
                         slots[s.i].push_back(s.slot);
                         work += s.ke - s.kb;
                     }
-                    if (work > p.q) { printf("overload g=%d kt=%d nbg=%d j=%d: %d > q=%d\n", g, kt, nbg, j, work, p.q); return 1; }
+                    if (work > p.full * kt + (p.gr > 0 ? p.q : 0)) { printf("overload g=%d kt=%d nbg=%d j=%d: %d > q=%d\n", g, kt, nbg, j, work, p.q); return 1; }
                 }
                 for (int x = 0; x < g * kt; ++x)
                     if (cover[x] != 1) { printf("coverage g=%d kt=%d nbg=%d tile %d slab %d: %d\n", g, kt, nbg, x / kt, x % kt, cover[x]); return 1; }
