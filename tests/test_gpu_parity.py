@@ -285,8 +285,8 @@ BALANCED = [
     W.small(C=256, I=9000, visual=(900, 600), text=(30, 12), keep=(450, 333), seed=24,
             name="bal-long-k-4tiles"),            # long K, remainder pieces spanning tiles
     W.small(C=4096, I=320, visual=(4400,), text=(30,), keep=(4100,), seed=25,
-            name="bal-17-mtiles-16-workgroups"),  # more m-tiles than workgroups per group: no
-                                                  # aligned chunk, every piece walks 2-3 tiles
+            name="bal-17-mtiles-16-workgroups"),  # more m-tiles than workgroups per group: a whole
+                                                  # tile per workgroup first, the 17th split 5 ways
 ]
 
 
