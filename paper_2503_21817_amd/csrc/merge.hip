@@ -67,15 +67,15 @@ __global__ __launch_bounds__(MG_THREADS) void sim_rowmean_kernel(const float* __
 // ---- kept[t] = 1 iff fewer than k tokens of the set have a lower average -----------------------
 __global__ __launch_bounds__(MG_THREADS) void merge_rank_kernel(const float* __restrict__ avg, SegTable st,
                                                                 int k, uint8_t* __restrict__ kept) {
-    __shared__ __align__(16) float sav[MERGE_MAX_N];
+    __shared__ __align__(16) uint32_t sav[MERGE_MAX_N];       // rank keys of the averages
     const int set = blockIdx.y;
     const int lo = st.off[set], n = st.off[set + 1] - lo;
     if ((int)blockIdx.x * MG_THREADS >= n) return;          // uniform over the workgroup
-    for (int u = threadIdx.x; u < n; u += MG_THREADS) sav[u] = avg[lo + u];
+    for (int u = threadIdx.x; u < n; u += MG_THREADS) sav[u] = rank_key<false>(avg[lo + u]);
     __syncthreads();
     const int t = blockIdx.x * MG_THREADS + threadIdx.x;
     if (t >= n) return;
-    const int lower = rank_in_lds<false>(sav, n, t, sav[t]);
+    const int lower = rank_in_lds(sav, n, t);
     kept[lo + t] = lower < k ? 1 : 0;
 }
 

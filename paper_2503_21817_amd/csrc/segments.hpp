@@ -59,23 +59,32 @@ __device__ __forceinline__ void unpack8s(const u32x4& v, float* f) {
     }
 }
 
-// Whether entry (v, u) comes before entry (vt, t) in the order "DESCENDING ? larger first :
-// smaller first", equal values ordered by index.  The order is total: a NaN comes after every
-// number (NaNs among themselves by index), so exactly min(k, n) entries have rank < k whatever
-// the values are.
+// The order of the rank counts: "DESCENDING ? larger first : smaller first", equal values (+0 and
+// -0 are equal) ordered by index.  The order is total: a NaN comes after every number (NaNs among
+// themselves by index), so exactly min(k, n) entries have rank < k whatever the values are.
+// rank_key maps a value to an unsigned key that increases along that order, so that "entry (v, u)
+// comes before entry (vt, t)" is one 64-bit comparison of (key, index) pairs: the rank loops do a
+// compare and an add per entry instead of the five float comparisons of the direct form (which
+// took the rank kernels from 28 to 82 us at 1024-token sets).
 template <bool DESCENDING>
-__device__ __forceinline__ bool ranks_before(float v, int u, float vt, int t) {
-    const bool vn = v != v, tn = vt != vt;
-    const bool first = DESCENDING ? v > vt : v < vt;           // false when either is NaN
-    const bool same = (v == vt) || (vn && tn);
-    return first || (!vn && tn) || (same && u < t);
+__device__ __forceinline__ uint32_t rank_key(float v) {
+    if (v != v) return 0xFFFFFFFFu;
+    uint32_t b = __float_as_uint(v);
+    if (b == 0x80000000u) b = 0u;                               // -0 == +0
+    // increasing with v; numbers (infinities included) map into [0x007FFFFF, 0xFF800000], and so does the
+    // complement of that range, so 0xFFFFFFFF is left to the NaNs in both orders
+    const uint32_t asc = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    return DESCENDING ? ~asc : asc;
 }
-// Number of entries u of vals[0..n) (an LDS array) that come before entry t in that order.
+__device__ __forceinline__ uint64_t rank_pair(uint32_t key, int index) {
+    return ((uint64_t)key << 32) | (uint32_t)index;
+}
+// Number of entries u of keys[0..n) (an LDS array of rank_key values) that come before entry t.
 // (One value per LDS read: a four-wide version was measured twice as slow.)
-template <bool DESCENDING>
-__device__ __forceinline__ int rank_in_lds(const float* vals, int n, int t, float vt) {
+__device__ __forceinline__ int rank_in_lds(const uint32_t* keys, int n, int t) {
+    const uint64_t mine = rank_pair(keys[t], t);
     int before = 0;
-    for (int u = 0; u < n; ++u) before += ranks_before<DESCENDING>(vals[u], u, vt, t) ? 1 : 0;
+    for (int u = 0; u < n; ++u) before += rank_pair(keys[u], u) < mine ? 1 : 0;
     return before;
 }
 

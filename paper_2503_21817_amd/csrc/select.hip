@@ -80,7 +80,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topn_kernel(
     const float* __restrict__ sim, const int32_t* __restrict__ seq_off, int B, int n_feat, int n_keep,
     const int32_t* __restrict__ n_keep_dev, uint8_t* __restrict__ mask,
     const int32_t* __restrict__ token_pos, uint8_t* __restrict__ skip_mask, int64_t T) {
-    __shared__ __align__(16) float ssim[SEL_LDS_SIMS];
+    __shared__ __align__(16) uint32_t ssim[SEL_LDS_SIMS];     // rank keys of the similarities
     int b, t0, nt;
     if (!locate_chunk<SEL_RANK_CH>(seq_off, B, n_feat, (int)blockIdx.x, b, t0, nt)) return;
     int lo, hi;
@@ -89,19 +89,17 @@ __global__ __launch_bounds__(SEL_THREADS) void select_topn_kernel(
     const int keep = n_keep_dev != nullptr ? n_keep_dev[b] : n_keep;
     const bool in_lds = n <= SEL_LDS_SIMS;
     if (in_lds) {
-        for (int u = threadIdx.x; u < n; u += SEL_THREADS) ssim[u] = sim[lo + u];
+        for (int u = threadIdx.x; u < n; u += SEL_THREADS) ssim[u] = rank_key<true>(sim[lo + u]);
         __syncthreads();
     }
     const int t = (t0 - lo) + threadIdx.x;           // index inside the sequence
     if ((int)threadIdx.x >= nt) return;
-    const float st = in_lds ? ssim[t] : sim[lo + t];
     int beats = 0;
     if (in_lds) {
-        beats = rank_in_lds<true>(ssim, n, t, st);
+        beats = rank_in_lds(ssim, n, t);
     } else {
-        for (int u = 0; u < n; ++u) {
-            beats += ranks_before<true>(sim[lo + u], u, st, t) ? 1 : 0;
-        }
+        const uint64_t mine = rank_pair(rank_key<true>(sim[lo + t]), t);
+        for (int u = 0; u < n; ++u) beats += rank_pair(rank_key<true>(sim[lo + u]), u) < mine ? 1 : 0;
     }
     const uint8_t m = beats < keep ? 0 : 1;
     mask[lo + t] = m;
