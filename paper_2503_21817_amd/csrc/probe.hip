@@ -55,8 +55,10 @@ __global__ __launch_bounds__(PROBE_THREADS) __attribute__((amdgpu_waves_per_eu(2
 #pragma unroll
         for (int i = 0; i < PROBE_MI; ++i)
 #pragma unroll
-            for (int j = 0; j < PROBE_NI; ++j)
+            for (int jj = 0; jj < PROBE_NI; ++jj) {
+                const int j = (i & 1) ? PROBE_NI - 1 - jj : jj;      // boustrophedon, as in the GEMM core
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+            }
     }
     const long long c1 = clock64(), w1 = wall_clock64();
     float s = 0.0f;
