@@ -275,6 +275,36 @@ def test_random_shapes_forward_backward(seed):
             assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, (k, r_host)
 
 
+@pytest.mark.parametrize("C,I", [(264, 200), (1096, 456), (456, 1096), (2056, 136), (192, 2056)],
+                         ids=lambda v: str(v))
+def test_k_ranges_that_end_inside_a_slab(C, I):
+    """256-row tiles (R > 256) with contraction lengths that are no multiple of the 64-deep K slab, from
+    3 to 33 slabs: the main loop runs its steady state (unmasked loads, offsets stepped per slab) up to
+    the slabs at the end of the K range - and, in the dXn GEMM, of each of its two operand pairs - which
+    take the guarded, masked path.  R = 300 is no multiple of 64 either (the weight-gradient GEMMs
+    contract over it)."""
+    w = W.small(C=C, I=I, visual=(330,), text=(12,), keep=(288,), seed=70 + C % 7, name=f"ktail-{C}-{I}")
+    assert w.R == 300
+    p = Problem(w, unit_gain=False, with_gain_tensor=True)
+    fo = O.skipffn_forward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.gain, w.eps)
+    bo = O.skipffn_backward(p.hidden, p.mask, p.wg, p.wu, p.wd, p.grad, p.gain, w.eps)
+    idx, sk = fo["idx"], p.mask != 0
+    for r_host in (True, False):
+        out, bufs = gpu_forward(p, R_host=r_host)
+        got = bits_of(out)
+        assert np.array_equal(got[sk], p.hidden[sk])
+        assert rel_l2(O.bf16_bits_to_f64(got[idx]), O.bf16_bits_to_f64(fo["out_bits"][idx])) < REL_L2_TOL
+        sv = bufs.saved_views(w.R)
+        for k in ("G", "U", "H"):
+            assert rel_l2(f64_of(sv[k]), fo[k]) < REL_L2_TOL, k
+        gh, dw = gpu_backward(p, bufs, R_host=r_host)
+        gb = bits_of(gh)
+        assert np.array_equal(gb[sk], p.grad[sk])
+        assert rel_l2(O.bf16_bits_to_f64(gb[idx]), O.bf16_bits_to_f64(bo["dx_bits"][idx])) < REL_L2_TOL
+        for t, k in zip(dw, ("dw_gate", "dw_up", "dw_down")):
+            assert rel_l2(f64_of(t), bo[k]) < REL_L2_TOL, (k, r_host)
+
+
 BALANCED = [
     # (workload, what it exercises)
     W.small(C=512, I=1368, visual=(300, 411), text=(20, 35), keep=(130, 212), seed=21,
